@@ -1,0 +1,6 @@
+"""fp64 CPU oracle of the PillarAttn hot path (test infrastructure only)."""
+from .pillar_oracle import (decode_tensor, e4m3_table, gather_request,
+                            verify_attn, select_topk, sparse_decode, run_all)
+
+__all__ = ["decode_tensor", "e4m3_table", "gather_request", "verify_attn",
+           "select_topk", "sparse_decode", "run_all"]

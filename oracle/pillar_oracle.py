@@ -1,0 +1,196 @@
+"""CPU oracle for the PillarAttn hot path.  TEST INFRASTRUCTURE ONLY.
+
+This file is the yardstick the HIP kernels are compared against.  It is plain
+numpy in float64, written from the paper's description (Section 4.1, and the
+page-size-1 view of sparse attention in Section 4.2) and shares nothing with
+the GPU code: no kernels, headers, tables or helpers.  Only tests, the smoke
+check and the benchmark's CPU-baseline leg may import it; the product path
+never does.
+
+What each function computes (the method's results are exactly defined
+quantities, so the oracle is the definition written out):
+
+  verify_attn    Section 4.1, "Overhead-free identification": full softmax
+                 attention of the k+1 speculative query positions over the
+                 whole KV-Cache of a request, causal among the new tokens,
+                 plus the attention-score statistic: the softmax probabilities
+                 averaged over the k+1 queries and over the query heads of
+                 one GQA group.
+  select_topk    Section 4.1: Top-K on those averaged scores gives the
+                 critical tokens of each (request, KV head).
+  sparse_decode  Sections 1 and 4.2: attention of one draft query restricted
+                 to the selected rows (paged attention at page size 1).
+
+Readings of points the paper leaves open (each is also listed in the design
+notes): the statistic averages over all k+1 verification rows with a uniform
+1/R weight, masked entries counting as zero, so it sums to one over a
+request's tokens; the context length includes the k+1 speculative tokens;
+selection is per (request, KV head) with budget min(K, L); ties go to the
+lower position; indices are returned in ascending position order.
+
+Pins (tests/test_oracle_*.py): an independent pure-Python triple loop on tiny
+inputs, a hand-derived rational example, closed forms (identical keys, one
+dominant key, context of only the speculative tokens), the invariants the
+definitions imply, and torch's float64 scaled_dot_product_attention on the
+un-paged tensors.  The paper prints no numeric example of this path, so
+beyond those pins parity is unpinned by the paper itself.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = ["decode_tensor", "e4m3_table", "gather_request", "verify_attn",
+           "select_topk", "sparse_decode", "run_all"]
+
+
+# ---------------------------------------------------------------------------
+# storage formats -> float64 (exact)
+# ---------------------------------------------------------------------------
+def e4m3_table() -> np.ndarray:
+    """All 256 values of OCP fp8 e4m3 (bias 7): normals (1+m/8)*2**(e-7),
+    subnormals (m/8)*2**-6, no infinities, S.1111.111 is NaN."""
+    t = np.empty(256, dtype=np.float64)
+    for code in range(256):
+        s = -1.0 if code & 0x80 else 1.0
+        e = (code >> 3) & 0xF
+        m = code & 0x7
+        if e == 0xF and m == 0x7:
+            v = np.nan
+        elif e == 0:
+            v = s * (m / 8.0) * 2.0 ** -6
+        else:
+            v = s * (1.0 + m / 8.0) * 2.0 ** (e - 7)
+        t[code] = v
+    return t
+
+
+_E4M3 = e4m3_table()
+
+
+def decode_tensor(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Stored tensor -> float64.  bf16 arrives as uint16 bit patterns, fp8 as
+    uint8 codes; both widen exactly."""
+    if dtype == "f32":
+        return np.asarray(x, dtype=np.float32).astype(np.float64)
+    if dtype == "bf16":
+        return (np.asarray(x, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    if dtype == "fp8_e4m3":
+        return _E4M3[np.asarray(x, dtype=np.uint8)]
+    raise ValueError(dtype)
+
+
+def gather_request(w, b: int):
+    """Un-page request b: K, V as float64 [L, Hkv, D].  Token t lives in page
+    block_table[b, t // P], slot t % P."""
+    L = int(w.seq_lens[b])
+    P = w.P
+    t = np.arange(L)
+    pages = w.block_table[b, t // P]
+    slots = t % P
+    k = decode_tensor(w.k_pool[pages, :, slots, :], w.kv_dtype)      # [L, Hkv, D]
+    v = decode_tensor(w.v_pool[pages, :, slots, :], w.kv_dtype)
+    if w.kv_dtype == "fp8_e4m3":
+        k = k * w.k_scale[pages].astype(np.float64)[:, :, None]
+        v = v * w.v_scale[pages].astype(np.float64)[:, :, None]
+    return k, v
+
+
+# ---------------------------------------------------------------------------
+def verify_attn(w, requests=None):
+    """Full attention of the verification step and the score statistic.
+
+    Returns out [B, k+1, Hq, D], lse [B, k+1, Hq] (natural log) and
+    scores [B, Hkv, max L] (zero beyond a request's length), all float64.
+    Query i of request b sits at position L_b-(k+1)+i and sees keys 0..that
+    position.  scores[b, g, t] is the mean over the R=(k+1)*G rows of group g
+    of the softmax probability the row puts on token t (zero where masked).
+    """
+    B, n_q, Hq, Hkv, D = w.B, w.n_q, w.Hq, w.Hkv, w.D
+    G = Hq // Hkv
+    R = n_q * G
+    Lmax = int(w.seq_lens.max()) if B else 0
+    q_all = decode_tensor(w.q, w.q_dtype)
+    out = np.zeros((B, n_q, Hq, D))
+    lse = np.zeros((B, n_q, Hq))
+    scores = np.zeros((B, Hkv, Lmax))
+    for b in (range(B) if requests is None else requests):
+        L = int(w.seq_lens[b])
+        k, v = gather_request(w, b)
+        pos = L - n_q + np.arange(n_q)                    # position of query i
+        visible = np.arange(L)[None, :] <= pos[:, None]   # [n_q, L]
+        for g in range(Hkv):
+            kg = k[:, g, :]                               # [L, D]
+            vg = v[:, g, :]
+            qg = q_all[b, :, g * G:(g + 1) * G, :]        # [n_q, G, D]
+            s = w.sm_scale * np.einsum("ihd,td->iht", qg, kg)      # [n_q, G, L]
+            s = np.where(visible[:, None, :], s, -np.inf)
+            m = s.max(axis=-1, keepdims=True)
+            e = np.exp(s - m)
+            l = e.sum(axis=-1, keepdims=True)
+            p = e / l                                     # rows sum to one
+            out[b, :, g * G:(g + 1) * G, :] = np.einsum("iht,td->ihd", p, vg)
+            lse[b, :, g * G:(g + 1) * G] = (m + np.log(l))[..., 0]
+            scores[b, g, :L] = p.sum(axis=(0, 1)) / R
+    return out, lse, scores
+
+
+def select_topk(scores, seq_lens, budgets, max_budget=None):
+    """Top-K positions per (request, KV head).
+
+    K' = min(budget_b, L_b) positions of largest score among 0..L_b-1, ties to
+    the lower position, returned ascending; indices [B, Hkv, max_budget] padded
+    with -1, counts [B] = K'.
+    """
+    scores = np.asarray(scores)
+    B, Hkv = scores.shape[0], scores.shape[1]
+    if max_budget is None:
+        max_budget = int(np.max(budgets)) if B else 0
+    idx = np.full((B, Hkv, max_budget), -1, dtype=np.int32)
+    counts = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        L = int(seq_lens[b])
+        kk = min(int(budgets[b]), L, max_budget)
+        counts[b] = kk
+        for g in range(Hkv):
+            order = np.argsort(-scores[b, g, :L], kind="stable")
+            idx[b, g, :kk] = np.sort(order[:kk])
+    return idx, counts
+
+
+def sparse_decode(w, indices, counts, requests=None):
+    """Draft attention over the selected rows only.
+
+    out [B, Hq, D], lse [B, Hq]: softmax over j < counts[b] of
+    sm_scale * <q_draft[b, h], K[b, indices[b, g, j], g]>, no mask.
+    """
+    B, Hq, Hkv, D = w.B, w.Hq, w.Hkv, w.D
+    G = Hq // Hkv
+    qd = decode_tensor(w.q_draft, w.q_dtype)
+    out = np.zeros((B, Hq, D))
+    lse = np.full((B, Hq), -np.inf)
+    for b in (range(B) if requests is None else requests):
+        n = int(counts[b])
+        if n == 0:
+            continue
+        k, v = gather_request(w, b)
+        for g in range(Hkv):
+            sel = np.asarray(indices[b, g, :n], dtype=np.int64)
+            ks = k[sel, g, :]
+            vs = v[sel, g, :]
+            for h in range(g * G, (g + 1) * G):
+                s = w.sm_scale * (ks @ qd[b, h])
+                m = s.max()
+                e = np.exp(s - m)
+                l = e.sum()
+                out[b, h] = (e / l) @ vs
+                lse[b, h] = m + np.log(l)
+    return out, lse
+
+
+def run_all(w):
+    """verify -> top-K -> one draft step, as one PillarAttn round runs them."""
+    out, lse, scores = verify_attn(w)
+    idx, counts = select_topk(scores, w.seq_lens, w.budgets)
+    d_out, d_lse = sparse_decode(w, idx, counts)
+    return dict(out=out, lse=lse, scores=scores, indices=idx, counts=counts,
+                draft_out=d_out, draft_lse=d_lse)
