@@ -1,0 +1,162 @@
+/*
+ * pillar.h -- C ABI of the PillarAttn hot path on MI355X (gfx950).
+ *
+ * One round of PillarAttn (paper Section 4.1) for one transformer layer:
+ *
+ *   pillar_verify_attn    full attention of the k+1 speculative query
+ *                         positions over each request's whole paged KV-Cache,
+ *                         which also emits the per-token attention-score
+ *                         statistic of the verification step;
+ *   pillar_select_topk    Top-K of that statistic per (request, KV head): the
+ *                         critical tokens of the next k draft steps;
+ *   pillar_sparse_decode  draft attention that loads only the selected rows
+ *                         (paged attention at page size 1, Section 4.2).
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer inside pillar_kv_t and every tensor argument is a DEVICE
+ *     pointer owned by the caller; the pillar_kv_t struct itself lives on the
+ *     host.  The library never allocates, frees or synchronises: all work is
+ *     enqueued on `hip_stream` (a hipStream_t, NULL = the default stream) and
+ *     the call returns at once.  Scratch memory comes in through `workspace`
+ *     (device, 256-byte aligned, at least pillar_workspace_bytes() bytes); its
+ *     contents are meaningless between calls and calls sharing one workspace
+ *     must be ordered on one stream.
+ *   - Return value: PILLAR_OK or a negative pillar_status.  Argument errors
+ *     are detected on the host before anything is launched, so a failed call
+ *     has no effect on the device.  Page ids and token indices stored in
+ *     device memory cannot be checked on the host: values outside their
+ *     documented ranges are undefined behaviour.
+ *   - Outputs are bit-identical from run to run for identical inputs.
+ *   - Tensors are dense C-order arrays unless a stride argument is given.
+ *   - bf16 is the upper half of an IEEE float32; fp8 is OCP e4m3 (bias 7,
+ *     largest finite 448, no infinities), dequantised as code * scale with
+ *     one fp32 scale per (page, KV head) for K and one for V.
+ *
+ * Supported shapes: head_dim 64 or 128; num_q_heads a multiple of
+ * num_kv_heads with group size G <= 16; page_size a power of two in 1..256;
+ * 0 <= spec_len_k <= 15 and (spec_len_k+1)*G <= 64.  Anything else returns
+ * PILLAR_EUNSUPPORTED.
+ */
+#ifndef PILLAR_H_
+#define PILLAR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PILLAR_OK = 0,
+  PILLAR_EINVAL = -1,        /* NULL pointer, non-positive size, inconsistent shapes */
+  PILLAR_EUNSUPPORTED = -2,  /* well-formed but outside the supported shapes/dtypes */
+  PILLAR_EWORKSPACE = -3,    /* workspace NULL, misaligned or too small */
+  PILLAR_EHIP = -4           /* the HIP runtime refused a launch */
+} pillar_status;
+
+typedef enum { PILLAR_F32 = 0, PILLAR_BF16 = 1, PILLAR_FP8_E4M3 = 2 } pillar_dtype;
+
+/* The paged KV-Cache of one layer and the requests that read it.
+ * Token t of request b is row  block_table[b*block_table_stride + t/page_size]
+ * (a page id), slot t % page_size; its K vector for KV head g starts at element
+ *   page*stride_page + g*stride_head + slot*stride_slot
+ * of k_pool (same for v_pool) and is head_dim contiguous elements.
+ * seq_lens[b] counts every token whose K/V is already in the pool, including
+ * the k+1 speculative tokens of a verification step. */
+typedef struct {
+  int32_t batch;               /* B  >= 1 */
+  int32_t num_q_heads;         /* Hq */
+  int32_t num_kv_heads;        /* Hkv, divides Hq */
+  int32_t head_dim;            /* D  */
+  int32_t page_size;           /* P  */
+  int32_t q_dtype;             /* PILLAR_F32 | PILLAR_BF16: type of q and of out */
+  int32_t kv_dtype;            /* PILLAR_F32 | PILLAR_BF16 | PILLAR_FP8_E4M3 */
+  float   sm_scale;            /* logit scale, normally 1/sqrt(D) */
+  const void* k_pool;          /* device */
+  const void* v_pool;          /* device */
+  int64_t stride_page;         /* element strides; stride_slot >= head_dim */
+  int64_t stride_head;
+  int64_t stride_slot;
+  const float* k_scale;        /* device [num_pages][Hkv], fp8 only, else NULL */
+  const float* v_scale;
+  int32_t num_pages;
+  int32_t block_table_stride;  /* row length of block_table, in entries */
+  const int32_t* block_table;  /* device [B][block_table_stride] */
+  const int32_t* seq_lens;     /* device [B], 1 <= seq_lens[b] <= max_seq_len */
+  int32_t max_seq_len;         /* host-known bound, <= block_table_stride*page_size */
+  int32_t reserved_;           /* set to 0 */
+} pillar_kv_t;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int pillar_version(void);
+
+/* Static, NUL-terminated description of a status code. */
+const char* pillar_status_string(int status);
+
+/* Bytes of workspace that any of the three stage calls below may need for
+ * this cache description, speculative length and largest budget.  Returns 0
+ * when the description is invalid.  Host-only arithmetic. */
+size_t pillar_workspace_bytes(const pillar_kv_t* kv, int32_t spec_len_k, int32_t max_budget);
+
+/* Verification attention (Section 4.1, "Overhead-free identification").
+ *   q      [B][k+1][Hq][D] q_dtype; row i is the query at position
+ *          seq_lens[b]-(k+1)+i and attends to tokens 0..that position.
+ *   out    [B][k+1][Hq][D] q_dtype: softmax(sm_scale * q K^T) V.
+ *   lse    [B][k+1][Hq] fp32 natural-log-sum-exp of the logits, or NULL.
+ *   scores [B][Hkv][score_stride] fp32, or NULL to skip the statistic:
+ *          scores[b][g][t] = mean over the (k+1)*G rows of KV head g of the
+ *          softmax probability that row assigns to token t (0 where the
+ *          causal mask hides t).  Entries t >= seq_lens[b] are not written.
+ *          score_stride >= max_seq_len. */
+int pillar_verify_attn(const pillar_kv_t* kv, const void* q, int32_t spec_len_k,
+                       void* out, float* lse, float* scores, int64_t score_stride,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Critical-token selection (Section 4.1: Top-K on the averaged scores).
+ *   scores   as written by pillar_verify_attn (all >= 0).
+ *   budgets  device [B]: sparsity budget K of each request (>= 0).
+ *   indices  device [B][Hkv][max_budget] int32: for each (b, g) the
+ *            K' = min(budgets[b], seq_lens[b], max_budget) positions of
+ *            largest score among 0..seq_lens[b]-1, equal scores resolved
+ *            towards the lower position, stored in ascending position order
+ *            and padded with -1.
+ *   counts   device [B] int32: K' of each request. */
+int pillar_select_topk(const float* scores, int64_t score_stride, const int32_t* seq_lens,
+                       const int32_t* budgets, int32_t batch, int32_t num_kv_heads,
+                       int32_t max_seq_len, int32_t max_budget,
+                       int32_t* indices, int32_t* counts,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Sparse draft attention (Sections 1 and 4.2): one query row per request
+ * attends to the listed rows only, no mask.
+ *   q        [B][Hq][D] q_dtype.
+ *   indices  device [B][Hkv][max_budget] int32 token positions in
+ *            0..seq_lens[b]-1, any order; counts device [B], the first
+ *            counts[b] entries of every head's list are used
+ *            (0 <= counts[b] <= max_budget).
+ *   out      [B][Hq][D] q_dtype (zeros where counts[b] == 0).
+ *   lse      [B][Hq] fp32 or NULL (-inf where counts[b] == 0). */
+int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* indices,
+                         const int32_t* counts, int32_t max_budget, void* out, float* lse,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Per-kernel timing for benchmarks.  pillar_profile_enable(1) makes every
+ * later launch of this library be bracketed by HIP events on its stream;
+ * pillar_profile_read synchronises the device, then fills up to `cap` entries
+ * (host memory) with the kernels seen since the last pillar_profile_reset,
+ * and returns how many there are.  Not meant for production paths: event
+ * creation allocates. */
+typedef struct {
+  char   name[48];
+  int64_t launches;
+  double total_ms;
+} pillar_kernel_time;
+void pillar_profile_enable(int on);
+void pillar_profile_reset(void);
+int  pillar_profile_read(pillar_kernel_time* entries, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PILLAR_H_ */

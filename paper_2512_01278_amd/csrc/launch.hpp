@@ -1,0 +1,63 @@
+// Host-side interfaces between the C ABI (pillar_api.hip) and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "common.hpp"
+
+namespace pillar {
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Brackets one kernel launch with HIP events when profiling is switched on.
+struct KernelTimer {
+  KernelTimer(const char* name, hipStream_t stream);
+  ~KernelTimer();
+  const char* name_;
+  hipStream_t stream_;
+  hipEvent_t start_ = nullptr;
+};
+
+struct VerifyArgs {
+  KvView kv;
+  const void* q;
+  void* out;
+  float* lse;            // may be null
+  float* scores;         // may be null
+  int64_t score_stride;
+  int32_t n_q;           // k+1
+  int32_t q_dtype, kv_dtype;
+  void* workspace;
+};
+
+struct DecodeArgs {
+  KvView kv;
+  const void* q;
+  const int32_t* indices;
+  const int32_t* counts;
+  int32_t max_budget;
+  void* out;
+  float* lse;            // may be null
+  int32_t q_dtype, kv_dtype;
+  void* workspace;
+};
+
+struct TopkArgs {
+  const float* scores;
+  int64_t score_stride;
+  const int32_t* seq_lens;
+  const int32_t* budgets;
+  int32_t batch, num_kv_heads, max_seq_len, max_budget;
+  int32_t* indices;
+  int32_t* counts;
+};
+
+// generic (any supported shape, fp32 arithmetic on the vector ALUs)
+size_t verify_generic_workspace(const KvView& kv, int n_q);
+hipError_t launch_verify_generic(const VerifyArgs& a, hipStream_t s);
+hipError_t launch_decode_generic(const DecodeArgs& a, hipStream_t s);
+hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
+
+}  // namespace pillar

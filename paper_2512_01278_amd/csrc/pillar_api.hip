@@ -1,0 +1,250 @@
+// C ABI of the PillarAttn hot path: argument validation on the host, then
+// dispatch to the kernel files.  Nothing here allocates device memory or
+// synchronises (the optional profiler aside).
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "launch.hpp"
+#include "pillar.h"
+
+namespace pillar {
+
+// ---------------------------------------------------------------- profiler --
+namespace {
+struct Pending {
+  const char* name;
+  hipEvent_t start, stop;
+};
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<Pending> g_pending;
+std::map<std::string, std::pair<int64_t, double>> g_totals;
+
+void drain_locked() {
+  for (auto& p : g_pending) {
+    float ms = 0.f;
+    if (hipEventSynchronize(p.stop) == hipSuccess && hipEventElapsedTime(&ms, p.start, p.stop) == hipSuccess) {
+      auto& e = g_totals[p.name];
+      e.first += 1;
+      e.second += ms;
+    }
+    (void)hipEventDestroy(p.start);
+    (void)hipEventDestroy(p.stop);
+  }
+  g_pending.clear();
+}
+}  // namespace
+
+KernelTimer::KernelTimer(const char* name, hipStream_t stream) : name_(name), stream_(stream) {
+  if (!g_prof_on) return;
+  if (hipEventCreate(&start_) != hipSuccess) { start_ = nullptr; return; }
+  (void)hipEventRecord(start_, stream_);
+}
+
+KernelTimer::~KernelTimer() {
+  if (!start_) return;
+  hipEvent_t stop;
+  if (hipEventCreate(&stop) != hipSuccess) { (void)hipEventDestroy(start_); return; }
+  (void)hipEventRecord(stop, stream_);
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_pending.push_back({name_, start_, stop});
+}
+
+// -------------------------------------------------------------- validation --
+namespace {
+
+bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+int check_kv(const pillar_kv_t* kv) {
+  if (!kv) return PILLAR_EINVAL;
+  if (kv->batch < 1 || kv->num_q_heads < 1 || kv->num_kv_heads < 1 || kv->head_dim < 1 || kv->page_size < 1 ||
+      kv->num_pages < 1 || kv->block_table_stride < 1 || kv->max_seq_len < 1)
+    return PILLAR_EINVAL;
+  if (kv->num_q_heads % kv->num_kv_heads != 0) return PILLAR_EINVAL;
+  if (!kv->k_pool || !kv->v_pool || !kv->block_table || !kv->seq_lens) return PILLAR_EINVAL;
+  if (kv->q_dtype != PILLAR_F32 && kv->q_dtype != PILLAR_BF16) return PILLAR_EUNSUPPORTED;
+  if (kv->kv_dtype != PILLAR_F32 && kv->kv_dtype != PILLAR_BF16 && kv->kv_dtype != PILLAR_FP8_E4M3)
+    return PILLAR_EUNSUPPORTED;
+  if (kv->kv_dtype == PILLAR_FP8_E4M3 && (!kv->k_scale || !kv->v_scale)) return PILLAR_EINVAL;
+  if (!(kv->sm_scale > 0.f) || !(kv->sm_scale < 1e30f)) return PILLAR_EINVAL;
+  if (kv->stride_slot < kv->head_dim || kv->stride_head < 1 || kv->stride_page < 1) return PILLAR_EINVAL;
+  if (static_cast<int64_t>(kv->max_seq_len) > static_cast<int64_t>(kv->block_table_stride) * kv->page_size)
+    return PILLAR_EINVAL;
+  if (kv->head_dim != 64 && kv->head_dim != 128) return PILLAR_EUNSUPPORTED;
+  if (!pow2(kv->page_size) || kv->page_size > 256) return PILLAR_EUNSUPPORTED;
+  if (kv->num_q_heads / kv->num_kv_heads > 16) return PILLAR_EUNSUPPORTED;
+  return PILLAR_OK;
+}
+
+int check_spec(const pillar_kv_t* kv, int spec_len_k) {
+  if (spec_len_k < 0) return PILLAR_EINVAL;
+  if (spec_len_k > 15) return PILLAR_EUNSUPPORTED;
+  if ((spec_len_k + 1) * (kv->num_q_heads / kv->num_kv_heads) > kMaxRows) return PILLAR_EUNSUPPORTED;
+  return PILLAR_OK;
+}
+
+KvView make_view(const pillar_kv_t* kv) {
+  KvView v;
+  v.k_pool = kv->k_pool;
+  v.v_pool = kv->v_pool;
+  v.k_scale = kv->k_scale;
+  v.v_scale = kv->v_scale;
+  v.block_table = kv->block_table;
+  v.seq_lens = kv->seq_lens;
+  v.stride_page = kv->stride_page;
+  v.stride_head = kv->stride_head;
+  v.stride_slot = kv->stride_slot;
+  v.batch = kv->batch;
+  v.num_q_heads = kv->num_q_heads;
+  v.num_kv_heads = kv->num_kv_heads;
+  v.head_dim = kv->head_dim;
+  v.page_size = kv->page_size;
+  v.page_shift = __builtin_ctz(static_cast<unsigned>(kv->page_size));
+  v.block_table_stride = kv->block_table_stride;
+  v.max_seq_len = kv->max_seq_len;
+  v.sm_scale = kv->sm_scale;
+  return v;
+}
+
+int check_workspace(const void* ws, size_t have, size_t need) {
+  if (need == 0) return PILLAR_OK;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || have < need) return PILLAR_EWORKSPACE;
+  return PILLAR_OK;
+}
+
+size_t verify_workspace(const KvView& v, int n_q) { return verify_generic_workspace(v, n_q); }
+
+}  // namespace
+}  // namespace pillar
+
+using namespace pillar;
+
+extern "C" {
+
+int pillar_version(void) { return 100; }
+
+const char* pillar_status_string(int status) {
+  switch (status) {
+    case PILLAR_OK: return "ok";
+    case PILLAR_EINVAL: return "invalid argument (null pointer, non-positive size or inconsistent shapes)";
+    case PILLAR_EUNSUPPORTED: return "shape or dtype outside the supported set";
+    case PILLAR_EWORKSPACE: return "workspace null, not 256-byte aligned, or too small";
+    case PILLAR_EHIP: return "HIP runtime error at launch";
+    default: return "unknown status";
+  }
+}
+
+size_t pillar_workspace_bytes(const pillar_kv_t* kv, int32_t spec_len_k, int32_t max_budget) {
+  if (check_kv(kv) != PILLAR_OK || check_spec(kv, spec_len_k) != PILLAR_OK || max_budget < 0) return 0;
+  const KvView v = make_view(kv);
+  size_t need = verify_workspace(v, spec_len_k + 1);
+  return need < 256 ? 256 : need;
+}
+
+int pillar_verify_attn(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, void* out, float* lse,
+                       float* scores, int64_t score_stride, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+  int rc = check_kv(kv);
+  if (rc != PILLAR_OK) return rc;
+  rc = check_spec(kv, spec_len_k);
+  if (rc != PILLAR_OK) return rc;
+  if (!q || !out) return PILLAR_EINVAL;
+  if (scores && score_stride < kv->max_seq_len) return PILLAR_EINVAL;
+  VerifyArgs a;
+  a.kv = make_view(kv);
+  a.q = q;
+  a.out = out;
+  a.lse = lse;
+  a.scores = scores;
+  a.score_stride = score_stride;
+  a.n_q = spec_len_k + 1;
+  a.q_dtype = kv->q_dtype;
+  a.kv_dtype = kv->kv_dtype;
+  a.workspace = workspace;
+  rc = check_workspace(workspace, workspace_bytes, verify_workspace(a.kv, a.n_q));
+  if (rc != PILLAR_OK) return rc;
+  const hipError_t e = launch_verify_generic(a, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+}
+
+int pillar_select_topk(const float* scores, int64_t score_stride, const int32_t* seq_lens, const int32_t* budgets,
+                       int32_t batch, int32_t num_kv_heads, int32_t max_seq_len, int32_t max_budget,
+                       int32_t* indices, int32_t* counts, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  if (!scores || !seq_lens || !budgets || !indices || !counts) return PILLAR_EINVAL;
+  if (batch < 1 || num_kv_heads < 1 || max_seq_len < 1 || max_budget < 1) return PILLAR_EINVAL;
+  if (score_stride < max_seq_len) return PILLAR_EINVAL;
+  TopkArgs a;
+  a.scores = scores;
+  a.score_stride = score_stride;
+  a.seq_lens = seq_lens;
+  a.budgets = budgets;
+  a.batch = batch;
+  a.num_kv_heads = num_kv_heads;
+  a.max_seq_len = max_seq_len;
+  a.max_budget = max_budget;
+  a.indices = indices;
+  a.counts = counts;
+  const hipError_t e = launch_topk(a, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+}
+
+int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* indices, const int32_t* counts,
+                         int32_t max_budget, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  int rc = check_kv(kv);
+  if (rc != PILLAR_OK) return rc;
+  if (!q || !indices || !counts || !out) return PILLAR_EINVAL;
+  if (max_budget < 1) return PILLAR_EINVAL;
+  (void)workspace;
+  (void)workspace_bytes;
+  DecodeArgs a;
+  a.kv = make_view(kv);
+  a.q = q;
+  a.indices = indices;
+  a.counts = counts;
+  a.max_budget = max_budget;
+  a.out = out;
+  a.lse = lse;
+  a.q_dtype = kv->q_dtype;
+  a.kv_dtype = kv->kv_dtype;
+  a.workspace = workspace;
+  const hipError_t e = launch_decode_generic(a, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+}
+
+void pillar_profile_enable(int on) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof_on = on != 0;
+}
+
+void pillar_profile_reset(void) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  drain_locked();
+  g_totals.clear();
+}
+
+int pillar_profile_read(pillar_kernel_time* entries, int cap) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  drain_locked();
+  int n = 0;
+  for (const auto& kvp : g_totals) {
+    if (entries && n < cap) {
+      std::memset(&entries[n], 0, sizeof(entries[n]));
+      std::strncpy(entries[n].name, kvp.first.c_str(), sizeof(entries[n].name) - 1);
+      entries[n].launches = kvp.second.first;
+      entries[n].total_ms = kvp.second.second;
+    }
+    ++n;
+  }
+  return n;
+}
+
+}  // extern "C"

@@ -1,0 +1,113 @@
+"""The C ABI without a GPU: the library loads, exports what the header
+declares, and rejects bad arguments on the host before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2512_01278_amd import binding as pb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # non-null, 256-aligned, never dereferenced on the host
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(pb.LIB_PATH):
+        from paper_2512_01278_amd.build import build
+        build(verbose=False)
+    return pb.load()
+
+
+def good_kv(**kw):
+    s = pb.pillar_kv_t()
+    s.batch, s.num_q_heads, s.num_kv_heads, s.head_dim, s.page_size = 4, 32, 8, 128, 16
+    s.q_dtype, s.kv_dtype, s.sm_scale = pb.PILLAR_BF16, pb.PILLAR_BF16, 0.088
+    s.k_pool = s.v_pool = s.block_table = s.seq_lens = FAKE
+    s.stride_page, s.stride_head, s.stride_slot = 8 * 16 * 128, 16 * 128, 128
+    s.num_pages, s.block_table_stride, s.max_seq_len = 1000, 64, 1024
+    for k, v in kw.items():
+        setattr(s, k, v)
+    return s
+
+
+def test_header_functions_are_all_exported(lib):
+    text = open(os.path.join(ROOT, "include", "pillar.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(pillar_[a-z_]+)\s*\(", text))
+    assert names == set(pb.EXPORTS), names ^ set(pb.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_struct_layout_matches_the_header():
+    assert C.sizeof(pb.pillar_kv_t) == 120 and pb.pillar_kv_t.k_pool.offset == 32
+    assert pb.pillar_kv_t.block_table.offset == 96 and pb.pillar_kv_t.max_seq_len.offset == 112
+    assert C.sizeof(pb.pillar_kernel_time) == 64
+
+
+def test_version_and_status_strings(lib):
+    assert lib.pillar_version() >= 100
+    seen = {lib.pillar_status_string(c) for c in (0, -1, -2, -3, -4)}
+    assert len(seen) == 5 and b"unknown" in lib.pillar_status_string(-99)
+
+
+def verify(lib, s, q=FAKE, k=4, out=FAKE, scores=FAKE, stride=1024, ws=FAKE, wsz=1 << 40):
+    return lib.pillar_verify_attn(C.byref(s), q, k, out, None, scores, stride, ws, wsz, None)
+
+
+def test_workspace_query(lib):
+    s = good_kv()
+    n = lib.pillar_workspace_bytes(C.byref(s), 4, 256)
+    assert n > 0 and n % 256 == 0
+    assert lib.pillar_workspace_bytes(C.byref(good_kv(batch=0)), 4, 256) == 0
+    assert lib.pillar_workspace_bytes(None, 4, 256) == 0
+    assert lib.pillar_workspace_bytes(C.byref(s), 16, 256) == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(batch=0), pb.PILLAR_EINVAL), (dict(num_kv_heads=5), pb.PILLAR_EINVAL),
+    (dict(k_pool=None), pb.PILLAR_EINVAL), (dict(seq_lens=None), pb.PILLAR_EINVAL),
+    (dict(kv_dtype=pb.PILLAR_FP8_E4M3), pb.PILLAR_EINVAL),           # fp8 without scales
+    (dict(sm_scale=0.0), pb.PILLAR_EINVAL), (dict(stride_slot=64), pb.PILLAR_EINVAL),
+    (dict(max_seq_len=64 * 16 + 1), pb.PILLAR_EINVAL),
+    (dict(head_dim=96, stride_slot=128), pb.PILLAR_EUNSUPPORTED), (dict(page_size=24), pb.PILLAR_EUNSUPPORTED),
+    (dict(q_dtype=pb.PILLAR_FP8_E4M3), pb.PILLAR_EUNSUPPORTED), (dict(kv_dtype=7), pb.PILLAR_EUNSUPPORTED),
+    (dict(num_q_heads=8 * 32), pb.PILLAR_EUNSUPPORTED),
+])
+def test_bad_cache_descriptions_are_rejected(lib, kw, code):
+    s = good_kv(**kw)
+    assert verify(lib, s) == code
+    assert lib.pillar_sparse_decode(C.byref(s), FAKE, FAKE, FAKE, 256, FAKE, None, FAKE, 1 << 40, None) == code
+
+
+def test_bad_call_arguments_are_rejected(lib):
+    s = good_kv()
+    assert verify(lib, s, q=None) == pb.PILLAR_EINVAL
+    assert verify(lib, s, out=None) == pb.PILLAR_EINVAL
+    assert verify(lib, s, k=-1) == pb.PILLAR_EINVAL
+    assert verify(lib, s, k=16) == pb.PILLAR_EUNSUPPORTED
+    assert verify(lib, good_kv(num_q_heads=64), k=8) == pb.PILLAR_EUNSUPPORTED     # 9*8 rows > 64
+    assert verify(lib, s, stride=1000) == pb.PILLAR_EINVAL
+    assert verify(lib, s, ws=None) == pb.PILLAR_EWORKSPACE
+    assert verify(lib, s, ws=FAKE + 8) == pb.PILLAR_EWORKSPACE
+    assert verify(lib, s, wsz=128) == pb.PILLAR_EWORKSPACE
+    assert lib.pillar_verify_attn(None, FAKE, 4, FAKE, None, None, 0, FAKE, 1 << 40, None) == pb.PILLAR_EINVAL
+    tk = lambda **k: lib.pillar_select_topk(k.get("scores", FAKE), k.get("stride", 1024), FAKE, k.get("budgets", FAKE),
+                                            k.get("batch", 4), 8, 1024, k.get("mb", 256), FAKE, k.get("counts", FAKE),
+                                            None, 0, None)
+    assert tk(scores=None) == pb.PILLAR_EINVAL and tk(budgets=None) == pb.PILLAR_EINVAL
+    assert tk(counts=None) == pb.PILLAR_EINVAL and tk(batch=0) == pb.PILLAR_EINVAL
+    assert tk(mb=0) == pb.PILLAR_EINVAL and tk(stride=512) == pb.PILLAR_EINVAL
+    sd = lambda **k: lib.pillar_sparse_decode(C.byref(s), k.get("q", FAKE), k.get("idx", FAKE), k.get("cnt", FAKE),
+                                              k.get("mb", 256), k.get("out", FAKE), None, FAKE, 1 << 40, None)
+    assert sd(q=None) == pb.PILLAR_EINVAL and sd(idx=None) == pb.PILLAR_EINVAL
+    assert sd(cnt=None) == pb.PILLAR_EINVAL and sd(out=None) == pb.PILLAR_EINVAL and sd(mb=0) == pb.PILLAR_EINVAL
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
+    monkeypatch.setattr(pb, "_lib", None)
+    monkeypatch.setattr(pb, "LIB_PATH", "/nonexistent/libpillar.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        pb.load()

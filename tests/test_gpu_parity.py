@@ -1,0 +1,167 @@
+"""GPU parity: every stage, through the C ABI, against the fp64 CPU oracle on
+the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import gen
+import oracle
+import paper_2512_01278_amd as pa
+from tests.harness import (GpuRun, check_out, check_topk_exact, compare_with_oracle, to_f64, LSE_ABS)
+
+pytestmark = pytest.mark.gpu
+
+
+def small(seed, **kw):
+    d = dict(name="small", seed=seed, B=3, Hq=8, Hkv=2, D=128, P=16, spec_k=2, q_dtype="bf16",
+             kv_dtype="bf16", seq_lens=[3, 130, 517], budgets=[2, 40, 64])
+    d.update(kw)
+    return gen.make_custom(**d)
+
+
+def round_trip(w, requests=None, what=""):
+    print(f"[case] {what or w.name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} D={w.D} P={w.P} k={w.spec_k} "
+          f"{w.q_dtype}/{w.kv_dtype} L={w.seq_lens[:6].tolist()} seed={w.seed}", flush=True)
+    run = GpuRun(w)
+    run.run_all()
+    rep = compare_with_oracle(w, run, requests, what or w.name)
+    print(f"[ok] {what or w.name}: {rep}", flush=True)
+    return run, rep
+
+
+# ------------------------------------------------------------ config 1 ------
+def test_config1_tiny_fp32():
+    round_trip(gen.make_workload(1), what="config1")
+
+
+# --------------------------------------------- small shapes, ragged tails ----
+@pytest.mark.parametrize("seed,kw", [
+    (101, dict()),
+    (102, dict(q_dtype="f32", kv_dtype="f32", D=64)),
+    (103, dict(kv_dtype="fp8_e4m3", Hq=16, Hkv=2, spec_k=4, seq_lens=[5, 255, 1000], budgets=[5, 16, 512])),
+    (104, dict(P=64, spec_k=8, Hq=8, Hkv=2, seq_lens=[9, 64, 700], budgets=[9, 64, 100])),
+    (105, dict(P=1, spec_k=0, Hq=4, Hkv=4, seq_lens=[1, 2, 129], budgets=[1, 1, 128])),
+    (106, dict(D=64, Hq=16, Hkv=1, spec_k=3, seq_lens=[4, 256, 257], budgets=[300, 1, 257])),
+    (107, dict(q_dtype="f32", kv_dtype="bf16", spec_k=15, Hq=4, Hkv=1, seq_lens=[16, 17, 400], budgets=[3, 3, 3])),
+    (108, dict(B=1, Hq=32, Hkv=8, spec_k=4, seq_lens=[2100], budgets=[128], sink_tokens=4)),
+    (109, dict(kv_dtype="fp8_e4m3", q_dtype="f32", D=64, P=4, seq_lens=[3, 4, 333], budgets=[1, 4, 33])),
+])
+def test_small_shapes(seed, kw):
+    round_trip(small(seed, **kw))
+
+
+# ------------------------------------------ the measured configs, reduced ----
+@pytest.mark.parametrize("cfg,batch", [(2, 2), (3, 4), (4, 1), (5, 2)])
+def test_config_reduced_batch(cfg, batch):
+    round_trip(gen.make_workload(cfg, batch=batch), what=f"config{cfg}[:{batch}]")
+
+
+# --------------------------- full size, sampled requests (bench's launch) ----
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_config_full_size_sampled(cfg):
+    w = gen.make_workload(cfg)
+    order = np.argsort(w.seq_lens, kind="stable")
+    sample = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2])})[: (2 if cfg == 4 else 3)]
+    run, rep = round_trip(w, requests=sample, what=f"config{cfg} full, requests {sample}")
+    # properties that hold at any size, on every request
+    scores = run.scores.cpu().numpy()
+    for b in range(w.B):
+        L = int(w.seq_lens[b])
+        tot = scores[b, :, :L].astype(np.float64).sum(-1)
+        assert np.all(np.abs(tot - 1.0) < 1e-4), f"request {b}: scores sum to {tot}"
+    idx, counts = run.indices.cpu().numpy(), run.counts.cpu().numpy()
+    assert np.array_equal(counts, np.minimum(w.budgets, w.seq_lens))
+    check_topk_exact(idx, counts, scores[:, :, :w.max_seq_len], w.seq_lens, w.budgets,
+                     list(range(0, w.B, max(1, w.B // 16))), f"config{cfg} full")
+    assert not torch.isnan(run.out.float()).any() and not torch.isnan(run.d_out.float()).any()
+
+
+# ----------------------------------------------------------- edge cases ------
+def test_outputs_are_bit_identical_from_run_to_run():
+    w = small(201, seq_lens=[40, 300, 1500], budgets=[8, 30, 100])
+    run = GpuRun(w)
+    run.run_all()
+    first = [t.clone() for t in (run.out, run.lse, run.scores, run.indices, run.counts, run.d_out, run.d_lse)]
+    run.run_all()
+    for a, b in zip(first, (run.out, run.lse, run.scores, run.indices, run.counts, run.d_out, run.d_lse)):
+        assert torch.equal(a.view(torch.uint8).flatten(), b.view(torch.uint8).flatten())
+
+
+def test_optional_outputs_may_be_null():
+    w = small(202)
+    run = GpuRun(w)
+    run.verify(with_scores=False, with_lse=False)
+    torch.cuda.synchronize()
+    assert torch.isnan(run.scores).all() and torch.isnan(run.lse).all()
+    want, _, _ = oracle.verify_attn(w)
+    check_out(to_f64(run.out), want, w.kv_dtype, "out without scores")
+
+
+def test_sparse_with_every_index_equals_verify_with_k0():
+    w = small(203, spec_k=0, seq_lens=[1, 77, 600], budgets=[1, 77, 600])
+    w.q_draft = w.q[:, 0].copy()
+    run = GpuRun(w)
+    run.run_all()
+    assert run.counts.cpu().tolist() == [1, 77, 600]
+    assert run.indices[2, 0].cpu().tolist() == list(range(600))
+    a, b = to_f64(run.out[:, 0]), to_f64(run.d_out)
+    assert np.abs(a - b).max() <= 1.6e-2            # two bf16 roundings of the same value
+    assert np.abs(to_f64(run.lse[:, 0]) - to_f64(run.d_lse)).max() <= LSE_ABS
+    compare_with_oracle(w, run)
+
+
+def test_strided_pool_layout_and_wide_block_table():
+    # pool stored [page][slot][head][dim]; the block table has spare columns
+    w = small(204, extra_table_cols=3)
+    run = GpuRun(w)
+    kv = run.dw.kv
+    kv.k_pool = kv.k_pool.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    kv.v_pool = kv.v_pool.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    assert kv.k_pool.stride(1) == w.D and kv.k_pool.stride(2) == w.Hkv * w.D
+    run.run_all()
+    compare_with_oracle(w, run)
+
+
+def test_empty_selection_and_zero_budget():
+    w = small(205, budgets=[0, 5, 0])
+    run = GpuRun(w)
+    run.run_all()
+    assert run.counts.cpu().tolist() == [0, 5, 0]
+    assert (run.indices[0] == -1).all() and (run.indices[2] == -1).all()
+    assert (run.d_out[0] == 0).all() and torch.isinf(run.d_lse[0]).all() and (run.d_lse[0] < 0).all()
+    compare_with_oracle(w, run, requests=[1])
+
+
+def test_topk_exact_ties_synthetic_scores():
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(7)
+    B, Hkv, L = 3, 2, 5000
+    s = (rng.integers(0, 6, size=(B, Hkv, L)) / 8.0).astype(np.float32)        # only six distinct values
+    s[2] = rng.random((Hkv, L)).astype(np.float32) ** 12                        # tiny values, wide exponent range
+    lens = np.array([5000, 4097, 1023], dtype=np.int32)
+    bud = np.array([700, 4097, 1], dtype=np.int32)
+    st = torch.from_numpy(s).to(dev)
+    idx = torch.full((B, Hkv, 4097), -9, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(B, dtype=torch.int32, device=dev)
+    pa.pillar_select_topk(st, torch.from_numpy(lens).to(dev), torch.from_numpy(bud).to(dev), 5000, 4097, idx, cnt)
+    torch.cuda.synchronize()
+    check_topk_exact(idx.cpu().numpy(), cnt.cpu().numpy(), s, lens, bud, [0, 1, 2], "ties")
+
+
+def test_decode_accepts_unsorted_and_repeated_free_lists():
+    w = small(206, seq_lens=[50, 300, 900], budgets=[10, 100, 300])
+    run = GpuRun(w)
+    run.verify(); run.topk()
+    torch.cuda.synchronize()
+    idx = run.indices.cpu().numpy().copy()
+    cnt = run.counts.cpu().numpy()
+    rng = np.random.default_rng(1)
+    for b in range(w.B):
+        for g in range(w.Hkv):
+            idx[b, g, :cnt[b]] = rng.permutation(idx[b, g, :cnt[b]])
+    ti = torch.from_numpy(idx).to(run.dev)
+    run.decode(indices=ti)
+    torch.cuda.synchronize()
+    want, want_l = oracle.sparse_decode(w, idx, cnt)
+    check_out(to_f64(run.d_out), want, w.kv_dtype, "shuffled list")
