@@ -1,0 +1,169 @@
+// The tile engine shared by the MFMA verification and draft kernels (gfx950).
+//
+// One wavefront owns a tile of 32 token rows of one KV head: it loads the K
+// and V rows from the paged pool with 16-byte, row-coalesced loads, parks
+// them in its private 16 KiB of LDS, and feeds v_mfma_f32_16x16x32_bf16:
+//
+//   S^T[token, row] = K[token, :] . Q[row, :]      A = K   (16 tokens x 32 dims)
+//                                                  B = Q^T (32 dims  x 16 rows)
+//   O^T[dim,  row] += V[token, dim] * P[row, token] A = V^T (16 dims  x 32 tokens)
+//                                                  B = P^T (32 tokens x 16 rows)
+//
+// "row" is one of the R = (k+1)*G query rows that share the KV head (paper
+// Section 4.1: the k+1 verification queries, times the query heads of one
+// group); a draft step has R = G.  Tokens sit on the MFMA's M side, so every
+// lane owns ONE query row (its column n = lane % 16) and the online-softmax
+// state of that row: the row maximum and sum need no cross-row traffic, and
+// the accumulator layout of S^T (lane group g = lane / 16 holds tokens 4g..4g+3)
+// is already the B-operand layout of P^T once the contraction index is
+// permuted, which costs nothing because V^T is read with the same permutation.
+//
+// LDS layout of a tile: 32 rows of 256 B, 16-byte chunks XOR-swizzled per row
+// so that the column-wise MFMA operand reads spread over all banks.
+#pragma once
+
+#include "common.hpp"
+
+namespace pillar {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kTileTokens = 32;
+constexpr int kHeadDim = 128;
+constexpr int kTileBytes = kTileTokens * kHeadDim * 2;   // one K or V tile in LDS (bf16)
+constexpr int kWaveLds = 2 * kTileBytes;                 // K tile + V tile
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// byte address of 16-byte chunk `c` of row `r` in a K tile / a V tile
+__device__ __forceinline__ int k_lds_addr(int r, int c) { return r * 256 + ((c ^ (r & 15)) << 4); }
+__device__ __forceinline__ int v_lds_addr(int r, int c) { return r * 256 + ((c ^ (((r >> 2) & 1) << 3)) << 4); }
+
+__device__ __forceinline__ float xor16(float v) { return __shfl_xor(v, 16, 64); }
+__device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
+
+// sum over the 16 lanes of a DPP row (all 16 lanes receive the total)
+__device__ __forceinline__ float row16_sum(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
+  return v;
+}
+
+// Registers of one 32-token tile in flight from HBM.
+//   bf16: 8 loads of 16 B for K and 8 for V per lane; load u covers token rows
+//         4u..4u+3, 16 lanes per 256-byte row.
+//   fp8 : 4 loads each; load u covers rows 8u..8u+7, 8 lanes per 128-byte row.
+template <bool FP8> struct TileRegs {
+  static constexpr int kLoads = FP8 ? 4 : 8;
+  u32x4 k[kLoads];
+  u32x4 v[kLoads];
+};
+
+// two packed fp8 e4m3 -> two packed bf16 (exact: e4m3 is a subset of bf16)
+__device__ __forceinline__ uint32_t fp8x2_to_bf16x2(uint32_t src, bool hi) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  const f32x2 f = hi ? __builtin_amdgcn_cvt_pk_f32_fp8(src, true) : __builtin_amdgcn_cvt_pk_f32_fp8(src, false);
+  // both values are exactly representable in bf16: truncation is exact
+  return (__float_as_uint(f.x) >> 16) | (__float_as_uint(f.y) & 0xffff0000u);
+}
+
+// Parks a tile in LDS as bf16 rows (fp8 rows are widened here, exactly).
+template <bool FP8>
+__device__ __forceinline__ void tile_to_lds(const TileRegs<FP8>& t, uint8_t* ktile, uint8_t* vtile, int lane) {
+  if constexpr (!FP8) {
+    const int c = lane & 15;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int r = 4 * u + (lane >> 4);
+      *reinterpret_cast<u32x4*>(ktile + k_lds_addr(r, c)) = t.k[u];
+      *reinterpret_cast<u32x4*>(vtile + v_lds_addr(r, c)) = t.v[u];
+    }
+  } else {
+    const int c = (lane & 7) * 2;          // 16 fp8 = two 16-byte bf16 chunks
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int r = 8 * u + (lane >> 3);
+      u32x4 lo, hi;
+      lo.x = fp8x2_to_bf16x2(t.k[u].x, false); lo.y = fp8x2_to_bf16x2(t.k[u].x, true);
+      lo.z = fp8x2_to_bf16x2(t.k[u].y, false); lo.w = fp8x2_to_bf16x2(t.k[u].y, true);
+      hi.x = fp8x2_to_bf16x2(t.k[u].z, false); hi.y = fp8x2_to_bf16x2(t.k[u].z, true);
+      hi.z = fp8x2_to_bf16x2(t.k[u].w, false); hi.w = fp8x2_to_bf16x2(t.k[u].w, true);
+      *reinterpret_cast<u32x4*>(ktile + k_lds_addr(r, c)) = lo;
+      *reinterpret_cast<u32x4*>(ktile + k_lds_addr(r, c + 1)) = hi;
+      lo.x = fp8x2_to_bf16x2(t.v[u].x, false); lo.y = fp8x2_to_bf16x2(t.v[u].x, true);
+      lo.z = fp8x2_to_bf16x2(t.v[u].y, false); lo.w = fp8x2_to_bf16x2(t.v[u].y, true);
+      hi.x = fp8x2_to_bf16x2(t.v[u].z, false); hi.y = fp8x2_to_bf16x2(t.v[u].z, true);
+      hi.z = fp8x2_to_bf16x2(t.v[u].w, false); hi.w = fp8x2_to_bf16x2(t.v[u].w, true);
+      *reinterpret_cast<u32x4*>(vtile + v_lds_addr(r, c)) = lo;
+      *reinterpret_cast<u32x4*>(vtile + v_lds_addr(r, c + 1)) = hi;
+    }
+  }
+}
+
+// S^T of the tile: acc[sub][rb] (sub = 16-token half, rb = 16-row block of Q).
+// qf[rb][s] holds, for lane (n, g), Q[16rb+n][32s+8g .. 32s+8g+7].
+template <int RB>
+__device__ __forceinline__ void tile_qk(const uint8_t* ktile, const bf16x8 (&qf)[RB][4], f32x4 (&acc)[2][RB], int lane) {
+  const int n = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[sub][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const u32x4 raw = *reinterpret_cast<const u32x4*>(ktile + k_lds_addr(16 * sub + n, 4 * s + g));
+      const bf16x8 a = as_bf16x8(raw);
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) acc[sub][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[rb][s], acc[sub][rb], 0, 0, 0);
+    }
+  }
+}
+
+// O^T += V^T P^T for the tile.  p[rb] is lane (n, g)'s B operand: elements
+// 0..3 = P[row n][token 4g+0..3], elements 4..7 = P[row n][token 16+4g+0..3].
+// The V^T operand is built from 8-byte LDS reads (4 dims of one token) and an
+// in-register 8x4 transpose, so lane m of dim block (half h, e) carries dim
+// 64h + 4m + e; the accumulator o[rb][4h+e] element i of lane (n, g) is
+// therefore O[row n][64h + 16g + 4i + e].
+template <int RB>
+__device__ __forceinline__ void tile_pv(const uint8_t* vtile, const bf16x8 (&p)[RB], f32x4 (&o)[RB][8], int lane) {
+  const int m = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    u32x2 w[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int tok = (j < 4) ? (4 * g + j) : (16 + 4 * g + (j - 4));
+      w[j] = *reinterpret_cast<const u32x2*>(vtile + v_lds_addr(tok, 8 * h + (m >> 1)) + (m & 1) * 8);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      u32x4 a;
+      const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+#pragma unroll
+      for (int pr = 0; pr < 4; ++pr) {
+        const uint32_t lo = (e & 2) ? w[2 * pr].y : w[2 * pr].x;
+        const uint32_t hi = (e & 2) ? w[2 * pr + 1].y : w[2 * pr + 1].x;
+        a[pr] = __builtin_amdgcn_perm(hi, lo, sel);
+      }
+      const bf16x8 av = as_bf16x8(a);
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) o[rb][4 * h + e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, p[rb], o[rb][4 * h + e], 0, 0, 0);
+    }
+  }
+}
+
+// eight fp32 -> packed bf16 B operand (round to nearest even)
+__device__ __forceinline__ bf16x8 pack_p(const f32x4& a, const f32x4& b) {
+  bf16x8 r;
+  r[0] = static_cast<__bf16>(a.x); r[1] = static_cast<__bf16>(a.y); r[2] = static_cast<__bf16>(a.z); r[3] = static_cast<__bf16>(a.w);
+  r[4] = static_cast<__bf16>(b.x); r[5] = static_cast<__bf16>(b.y); r[6] = static_cast<__bf16>(b.z); r[7] = static_cast<__bf16>(b.w);
+  return r;
+}
+
+}  // namespace pillar

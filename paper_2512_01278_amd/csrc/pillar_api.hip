@@ -3,6 +3,7 @@
 // synchronises (the optional profiler aside).
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -117,9 +118,21 @@ int check_workspace(const void* ws, size_t have, size_t need) {
   return PILLAR_OK;
 }
 
-size_t verify_workspace(const KvView& v, int n_q) { return verify_generic_workspace(v, n_q); }
+size_t verify_workspace(const KvView& v, int n_q) {
+  const size_t a = verify_generic_workspace(v, n_q);
+  const size_t b = (v.head_dim == 128 && v.page_size >= 16) ? verify_mfma_workspace(v, n_q) : 0;
+  return a > b ? a : b;
+}
 
 }  // namespace
+
+bool force_generic() {
+  static const bool on = [] {
+    const char* e = std::getenv("PILLAR_FORCE_GENERIC");
+    return e && e[0] == '1';
+  }();
+  return on;
+}
 }  // namespace pillar
 
 using namespace pillar;
@@ -168,7 +181,9 @@ int pillar_verify_attn(const pillar_kv_t* kv, const void* q, int32_t spec_len_k,
   a.workspace = workspace;
   rc = check_workspace(workspace, workspace_bytes, verify_workspace(a.kv, a.n_q));
   if (rc != PILLAR_OK) return rc;
-  const hipError_t e = launch_verify_generic(a, static_cast<hipStream_t>(hip_stream));
+  const hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const hipError_t e = (!force_generic() && verify_mfma_supported(a)) ? launch_verify_mfma(a, st)
+                                                                       : launch_verify_generic(a, st);
   return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
 }
 
