@@ -1,0 +1,336 @@
+// Sparse draft attention on the matrix cores (bf16 queries, bf16 or fp8 KV,
+// head_dim 128).
+//
+// Paper Sections 1 and 4.2: a draft step loads only the critical tokens chosen
+// at the last verification; addressing the KV-Cache row by row ("page size 1")
+// makes it the same pipeline as full attention, driven by an index list.  The
+// step is a gather of 256-byte rows (128-byte for fp8) and is bound by memory
+// latency, so the kernel's job is to get every row load of a (request, KV head)
+// in flight as early as possible; the G query rows of the group ride along as
+// one 16-row MFMA block (the tile engine of mfma_tile.hpp with R = G).
+//
+// One workgroup per (request, KV head, split of the index list); its four
+// wavefronts take 32-row tiles round-robin.  Lists that fit one split are
+// finished in the kernel; longer lists leave (max, sum, O) partials that a
+// second small kernel combines.
+#include "launch.hpp"
+#include "mfma_tile.hpp"
+
+namespace pillar {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+constexpr int kLdsBytes = kWaves * kWaveLds;
+
+struct DecWs {
+  float* part_m;   // [B][Hkv][nsplit][16]  log2 domain
+  float* part_l;   // [B][Hkv][nsplit][16]
+  float* part_o;   // [B][Hkv][nsplit][G][128]
+};
+
+struct Gather {
+  int tok;      // lane j < 32: token position of row j of the tile
+  int page;     // its page id
+  float ks, vs; // fp8 only: dequantisation scales of that row
+};
+
+template <bool FP8>
+__device__ __forceinline__ Gather load_gather(const KvView& kv, const int32_t* list, int b, int g, int j_first, int j_end, int lane) {
+  Gather gt;
+  const int j = min(j_first + (lane & 31), j_end - 1);      // rows past the end repeat the last one (masked later)
+  gt.tok = list[j];
+  gt.page = kv.block_table[static_cast<int64_t>(b) * kv.block_table_stride + (gt.tok >> kv.page_shift)];
+  gt.ks = gt.vs = 1.f;
+  if constexpr (FP8) {
+    gt.ks = kv.k_scale[static_cast<int64_t>(gt.page) * kv.num_kv_heads + g];
+    gt.vs = kv.v_scale[static_cast<int64_t>(gt.page) * kv.num_kv_heads + g];
+  }
+  return gt;
+}
+
+template <bool FP8>
+__device__ __forceinline__ void issue_gather(const KvView& kv, int g, const Gather& gt, TileRegs<FP8>& t, int lane) {
+  constexpr int kRowsPerLoad = FP8 ? 8 : 4;
+  constexpr int kLanesPerRow = FP8 ? 8 : 16;
+  const int col = (lane % kLanesPerRow) * 16;
+  const char* kp = static_cast<const char*>(kv.k_pool);
+  const char* vp = static_cast<const char*>(kv.v_pool);
+  const int esz = FP8 ? 1 : 2;
+#pragma unroll
+  for (int u = 0; u < TileRegs<FP8>::kLoads; ++u) {
+    const int row = kRowsPerLoad * u + lane / kLanesPerRow;
+    const int tok = __shfl(gt.tok, row, 64);
+    const int page = __shfl(gt.page, row, 64);
+    const int64_t off = (static_cast<int64_t>(page) * kv.stride_page + static_cast<int64_t>(g) * kv.stride_head +
+                         static_cast<int64_t>(tok & (kv.page_size - 1)) * kv.stride_slot) * esz + col;
+    t.k[u] = *reinterpret_cast<const u32x4*>(kp + off);
+    t.v[u] = *reinterpret_cast<const u32x4*>(vp + off);
+  }
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  return f32_to_bf16(a) | (static_cast<uint32_t>(f32_to_bf16(b)) << 16);
+}
+
+template <bool FP8>
+__global__ __launch_bounds__(kThreads, 2) void decode_split_mfma(DecodeArgs a, DecWs ws, int split_rows, int nsplit_max) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  __shared__ float s_m[kWaves][16], s_l[kWaves][16];
+  const KvView& kv = a.kv;
+  const int b = blockIdx.z, g = blockIdx.y, sp = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 15, g4 = lane >> 4;
+  const int G = kv.num_q_heads / kv.num_kv_heads;
+  const int count = min(max(a.counts[b], 0), a.max_budget);
+  uint16_t* out = static_cast<uint16_t*>(a.out);
+  if (count == 0) {
+    if (sp == 0) {
+      for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kThreads)
+        out[(static_cast<int64_t>(b) * kv.num_q_heads + g * G) * kHeadDim + idx] = 0;
+      if (a.lse && threadIdx.x < G) a.lse[static_cast<int64_t>(b) * kv.num_q_heads + g * G + threadIdx.x] = -INFINITY;
+    }
+    return;
+  }
+  const int j_begin = sp * split_rows;
+  if (j_begin >= count) return;
+  const int j_end = min(count, j_begin + split_rows);
+  const int nsplit = (count + split_rows - 1) / split_rows;
+  const int ntiles = (j_end - j_begin + kTileTokens - 1) / kTileTokens;
+  const int32_t* list = a.indices + (static_cast<int64_t>(b) * kv.num_kv_heads + g) * a.max_budget;
+  uint8_t* ktile = smem + wave * kWaveLds;
+  uint8_t* vtile = ktile + kTileBytes;
+  const float c2 = kv.sm_scale * kLog2e;
+
+  f32x4 o[1][8];
+#pragma unroll
+  for (int d = 0; d < 8; ++d) o[0][d] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;
+
+  if (wave < ntiles) {
+    // B operand: lane (n, g4) holds Q[row n][32s + 8 g4 .. +7]
+    bf16x8 qf[1][4];
+    const uint16_t* qrow = static_cast<const uint16_t*>(a.q) + (static_cast<int64_t>(b) * kv.num_q_heads + g * G + n) * kHeadDim;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (n < G) v = *reinterpret_cast<const u32x4*>(qrow + 32 * s + 8 * g4);
+      qf[0][s] = as_bf16x8(v);
+    }
+    Gather cur = load_gather<FP8>(kv, list, b, g, j_begin + wave * kTileTokens, j_end, lane);
+    TileRegs<FP8> regs;
+    issue_gather<FP8>(kv, g, cur, regs, lane);
+    for (int ti = wave; ti < ntiles; ti += kWaves) {
+      const int jb = j_begin + ti * kTileTokens;
+      const bool more = ti + kWaves < ntiles;
+      Gather nxt = cur;
+      if (more) nxt = load_gather<FP8>(kv, list, b, g, jb + kWaves * kTileTokens, j_end, lane);
+      tile_to_lds<FP8>(regs, ktile, vtile, lane);
+      if (more) issue_gather<FP8>(kv, g, nxt, regs, lane);
+
+      f32x4 s[2][1];
+      tile_qk<1>(ktile, qf, s, lane);
+      f32x4 vsc[2];
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int slot = 16 * sub + 4 * g4 + i;
+          float sc = c2;
+          vsc[sub][i] = 1.f;
+          if constexpr (FP8) {
+            sc *= __shfl(cur.ks, slot, 64);
+            vsc[sub][i] = __shfl(cur.vs, slot, 64);
+          }
+          float v = s[sub][0][i] * sc;
+          if (jb + slot >= j_end) v = -INFINITY;
+          s[sub][0][i] = v;
+        }
+      }
+      float mx = fmaxf(fmaxf(fmaxf(s[0][0][0], s[0][0][1]), fmaxf(s[0][0][2], s[0][0][3])),
+                       fmaxf(fmaxf(s[1][0][0], s[1][0][1]), fmaxf(s[1][0][2], s[1][0][3])));
+      mx = fmaxf(mx, xor16(mx));
+      mx = fmaxf(mx, xor32(mx));
+      const float m_new = fmaxf(m_run, mx);              // finite: every tile has a valid row
+      const float alpha = exp2f(m_run - m_new);
+      f32x4 p0, p1;
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        p0[i] = exp2f(s[0][0][i] - m_new);
+        p1[i] = exp2f(s[1][0][i] - m_new);
+        sum += p0[i] + p1[i];
+      }
+      l_run = l_run * alpha + sum;
+      m_run = m_new;
+#pragma unroll
+      for (int d = 0; d < 8; ++d) o[0][d] *= alpha;
+      if constexpr (FP8) { p0 *= vsc[0]; p1 *= vsc[1]; }
+      bf16x8 p[1];
+      p[0] = pack_p(p0, p1);
+      tile_pv<1>(vtile, p, o, lane);
+      cur = nxt;
+    }
+    l_run += xor16(l_run);
+    l_run += xor32(l_run);
+  }
+
+  // ---- combine the four wavefronts ----
+  if (g4 == 0) { s_m[wave][n] = m_run; s_l[wave][n] = l_run; }
+  __syncthreads();
+  float m_all = -INFINITY;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) m_all = fmaxf(m_all, s_m[w][n]);
+  float l_all = 0.f;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) l_all += s_l[w][n] * exp2f(s_m[w][n] - m_all);
+  const float mine = exp2f(m_run - m_all);
+#pragma unroll
+  for (int d = 0; d < 8; ++d) o[0][d] *= mine;
+  f32x4* xch = reinterpret_cast<f32x4*>(smem);
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    const int from = round == 0 ? 2 : 1, to = round == 0 ? 4 : 2;
+    __syncthreads();
+    if (wave >= from && wave < to) {
+#pragma unroll
+      for (int d = 0; d < 8; ++d) xch[(wave - from) * 512 + d * 64 + lane] = o[0][d];
+    }
+    __syncthreads();
+    if (wave < to - from && wave < from) {
+#pragma unroll
+      for (int d = 0; d < 8; ++d) o[0][d] += xch[wave * 512 + d * 64 + lane];
+    }
+  }
+  if (wave != 0 || n >= G) return;
+  const int64_t row = static_cast<int64_t>(b) * kv.num_q_heads + g * G + n;
+  if (nsplit == 1) {
+    const float inv = 1.0f / l_all;
+    uint16_t* dst = out + row * kHeadDim;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      u32x2 pk;
+      pk.x = pack_bf16x2(o[0][db][0] * inv, o[0][db][1] * inv);
+      pk.y = pack_bf16x2(o[0][db][2] * inv, o[0][db][3] * inv);
+      *reinterpret_cast<u32x2*>(dst + 16 * db + 4 * g4) = pk;
+    }
+    if (a.lse && g4 == 0) a.lse[row] = (m_all + log2f(l_all)) * kLn2;
+  } else {
+    const int64_t slot = (static_cast<int64_t>(b) * kv.num_kv_heads + g) * nsplit_max + sp;
+    if (g4 == 0) { ws.part_m[slot * 16 + n] = m_all; ws.part_l[slot * 16 + n] = l_all; }
+    float* dst = ws.part_o + (slot * G + n) * kHeadDim;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + 16 * db + 4 * g4) = o[0][db];
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void decode_merge_mfma(DecodeArgs a, DecWs ws, int split_rows, int nsplit_max) {
+  const KvView& kv = a.kv;
+  const int b = blockIdx.y, g = blockIdx.x;
+  const int G = kv.num_q_heads / kv.num_kv_heads;
+  const int count = min(max(a.counts[b], 0), a.max_budget);
+  const int nsplit = (count + split_rows - 1) / split_rows;
+  if (nsplit <= 1) return;
+  uint16_t* out = static_cast<uint16_t*>(a.out);
+  const int64_t base = (static_cast<int64_t>(b) * kv.num_kv_heads + g) * nsplit_max;
+  for (int idx = threadIdx.x; idx < G * (kHeadDim / 4); idx += kThreads) {
+    const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
+    float m = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) m = fmaxf(m, ws.part_m[(base + s) * 16 + r]);
+    float l = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < nsplit; ++s) {
+      const float w = exp2f(ws.part_m[(base + s) * 16 + r] - m);
+      l = fmaf(ws.part_l[(base + s) * 16 + r], w, l);
+      acc += *reinterpret_cast<const f32x4*>(ws.part_o + ((base + s) * G + r) * kHeadDim + 4 * d4) * w;
+    }
+    const float inv = 1.0f / l;
+    const int64_t row = static_cast<int64_t>(b) * kv.num_q_heads + g * G + r;
+    u32x2 pk;
+    pk.x = pack_bf16x2(acc.x * inv, acc.y * inv);
+    pk.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+    *reinterpret_cast<u32x2*>(out + row * kHeadDim + 4 * d4) = pk;
+    if (d4 == 0 && a.lse) a.lse[row] = (m + log2f(l)) * kLn2;
+  }
+}
+
+// rows of the index list per workgroup: enough workgroups to fill the chip,
+// few enough that the partials stay a small fraction of the gathered bytes
+int pick_split_rows(const KvView& kv, int max_budget) {
+  const int64_t pairs = static_cast<int64_t>(kv.batch) * kv.num_kv_heads;
+  const int64_t target_wgs = 1536;
+  int64_t rows = (pairs * max_budget + target_wgs - 1) / target_wgs;
+  rows = (rows + kTileTokens - 1) / kTileTokens * kTileTokens;
+  if (rows < 128) rows = 128;
+  if (rows > 1024) rows = 1024;
+  return static_cast<int>(rows);
+}
+
+DecWs carve(const KvView& kv, int max_budget, void* workspace, size_t* total) {
+  const int split_rows = pick_split_rows(kv, max_budget);
+  const size_t nsplit = (static_cast<size_t>(max_budget) + split_rows - 1) / split_rows;
+  const size_t pairs = static_cast<size_t>(kv.batch) * kv.num_kv_heads;
+  const size_t G = kv.num_q_heads / kv.num_kv_heads;
+  char* p = static_cast<char*>(workspace);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { char* r = p ? p + off : nullptr; off += align_up(bytes, 256); return r; };
+  DecWs w;
+  w.part_m = reinterpret_cast<float*>(take(pairs * nsplit * 16 * 4));
+  w.part_l = reinterpret_cast<float*>(take(pairs * nsplit * 16 * 4));
+  w.part_o = reinterpret_cast<float*>(take(pairs * nsplit * G * kHeadDim * 4));
+  if (total) *total = off;
+  return w;
+}
+
+template <bool FP8>
+hipError_t run(const DecodeArgs& a, hipStream_t st) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_split_mfma<FP8>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const KvView& kv = a.kv;
+  const int split_rows = pick_split_rows(kv, a.max_budget);
+  const int nsplit = (a.max_budget + split_rows - 1) / split_rows;
+  const DecWs ws = carve(kv, a.max_budget, a.workspace, nullptr);
+  {
+    KernelTimer t("decode_split_mfma", st);
+    hipLaunchKernelGGL((decode_split_mfma<FP8>), dim3(nsplit, kv.num_kv_heads, kv.batch), dim3(kThreads), kLdsBytes, st,
+                       a, ws, split_rows, nsplit);
+  }
+  if (nsplit > 1) {
+    KernelTimer t("decode_merge_mfma", st);
+    hipLaunchKernelGGL(decode_merge_mfma, dim3(kv.num_kv_heads, kv.batch), dim3(kThreads), 0, st, a, ws, split_rows, nsplit);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool decode_mfma_supported(const DecodeArgs& a) {
+  const KvView& kv = a.kv;
+  if (a.q_dtype != PILLAR_BF16) return false;
+  if (a.kv_dtype != PILLAR_BF16 && a.kv_dtype != PILLAR_FP8_E4M3) return false;
+  if (kv.head_dim != kHeadDim) return false;
+  const int64_t align = a.kv_dtype == PILLAR_BF16 ? 8 : 16;
+  if (kv.stride_page % align || kv.stride_head % align || kv.stride_slot % align) return false;
+  if ((reinterpret_cast<uintptr_t>(kv.k_pool) | reinterpret_cast<uintptr_t>(kv.v_pool) | reinterpret_cast<uintptr_t>(a.q) |
+       reinterpret_cast<uintptr_t>(a.out)) & 15u)
+    return false;
+  return true;
+}
+
+size_t decode_mfma_workspace(const KvView& kv, int max_budget) {
+  if (max_budget < 1) return 0;
+  size_t total = 0;
+  carve(kv, max_budget, nullptr, &total);
+  return total;
+}
+
+hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s) {
+  return a.kv_dtype == PILLAR_FP8_E4M3 ? run<true>(a, s) : run<false>(a, s);
+}
+
+}  // namespace pillar

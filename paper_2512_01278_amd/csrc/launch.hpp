@@ -64,6 +64,9 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
 bool verify_mfma_supported(const VerifyArgs& a);
 size_t verify_mfma_workspace(const KvView& kv, int n_q);
 hipError_t launch_verify_mfma(const VerifyArgs& a, hipStream_t s);
+bool decode_mfma_supported(const DecodeArgs& a);
+size_t decode_mfma_workspace(const KvView& kv, int max_budget);
+hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s);
 
 // true when the environment asks for the generic kernels everywhere
 bool force_generic();

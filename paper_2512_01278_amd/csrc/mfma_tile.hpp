@@ -19,7 +19,8 @@
 // permuted, which costs nothing because V^T is read with the same permutation.
 //
 // LDS layout of a tile: 32 rows of 256 B, 16-byte chunks XOR-swizzled per row
-// so that the column-wise MFMA operand reads spread over all banks.
+// so that the column-wise MFMA operand reads (K) and the transposing reads (V)
+// spread over all banks.
 #pragma once
 
 #include "common.hpp"
@@ -40,7 +41,7 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 
 // byte address of 16-byte chunk `c` of row `r` in a K tile / a V tile
 __device__ __forceinline__ int k_lds_addr(int r, int c) { return r * 256 + ((c ^ (r & 15)) << 4); }
-__device__ __forceinline__ int v_lds_addr(int r, int c) { return r * 256 + ((c ^ (((r >> 2) & 1) << 3)) << 4); }
+__device__ __forceinline__ int v_lds_addr(int r, int c) { return r * 256 + ((c ^ (((r & 3) << 1) | (((r >> 2) & 1) << 3))) << 4); }
 
 __device__ __forceinline__ float xor16(float v) { return __shfl_xor(v, 16, 64); }
 __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
@@ -72,16 +73,24 @@ __device__ __forceinline__ uint32_t fp8x2_to_bf16x2(uint32_t src, bool hi) {
   return (__float_as_uint(f.x) >> 16) | (__float_as_uint(f.y) & 0xffff0000u);
 }
 
-// Parks a tile in LDS as bf16 rows (fp8 rows are widened here, exactly).
-template <bool FP8>
-__device__ __forceinline__ void tile_to_lds(const TileRegs<FP8>& t, uint8_t* ktile, uint8_t* vtile, int lane) {
+// sixteen fp8 -> two 16-byte chunks of bf16
+__device__ __forceinline__ void widen_fp8x16(const u32x4& src, u32x4& lo, u32x4& hi) {
+  lo.x = fp8x2_to_bf16x2(src.x, false); lo.y = fp8x2_to_bf16x2(src.x, true);
+  lo.z = fp8x2_to_bf16x2(src.y, false); lo.w = fp8x2_to_bf16x2(src.y, true);
+  hi.x = fp8x2_to_bf16x2(src.z, false); hi.y = fp8x2_to_bf16x2(src.z, true);
+  hi.z = fp8x2_to_bf16x2(src.w, false); hi.w = fp8x2_to_bf16x2(src.w, true);
+}
+
+// Parks the K (IS_V = false) or V rows of a tile in LDS as bf16 rows (fp8 rows
+// are widened here, exactly).
+template <bool FP8, bool IS_V>
+__device__ __forceinline__ void rows_to_lds(const u32x4 (&regs)[TileRegs<FP8>::kLoads], uint8_t* tile, int lane) {
   if constexpr (!FP8) {
     const int c = lane & 15;
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int r = 4 * u + (lane >> 4);
-      *reinterpret_cast<u32x4*>(ktile + k_lds_addr(r, c)) = t.k[u];
-      *reinterpret_cast<u32x4*>(vtile + v_lds_addr(r, c)) = t.v[u];
+      *reinterpret_cast<u32x4*>(tile + (IS_V ? v_lds_addr(r, c) : k_lds_addr(r, c))) = regs[u];
     }
   } else {
     const int c = (lane & 7) * 2;          // 16 fp8 = two 16-byte bf16 chunks
@@ -89,20 +98,17 @@ __device__ __forceinline__ void tile_to_lds(const TileRegs<FP8>& t, uint8_t* kti
     for (int u = 0; u < 4; ++u) {
       const int r = 8 * u + (lane >> 3);
       u32x4 lo, hi;
-      lo.x = fp8x2_to_bf16x2(t.k[u].x, false); lo.y = fp8x2_to_bf16x2(t.k[u].x, true);
-      lo.z = fp8x2_to_bf16x2(t.k[u].y, false); lo.w = fp8x2_to_bf16x2(t.k[u].y, true);
-      hi.x = fp8x2_to_bf16x2(t.k[u].z, false); hi.y = fp8x2_to_bf16x2(t.k[u].z, true);
-      hi.z = fp8x2_to_bf16x2(t.k[u].w, false); hi.w = fp8x2_to_bf16x2(t.k[u].w, true);
-      *reinterpret_cast<u32x4*>(ktile + k_lds_addr(r, c)) = lo;
-      *reinterpret_cast<u32x4*>(ktile + k_lds_addr(r, c + 1)) = hi;
-      lo.x = fp8x2_to_bf16x2(t.v[u].x, false); lo.y = fp8x2_to_bf16x2(t.v[u].x, true);
-      lo.z = fp8x2_to_bf16x2(t.v[u].y, false); lo.w = fp8x2_to_bf16x2(t.v[u].y, true);
-      hi.x = fp8x2_to_bf16x2(t.v[u].z, false); hi.y = fp8x2_to_bf16x2(t.v[u].z, true);
-      hi.z = fp8x2_to_bf16x2(t.v[u].w, false); hi.w = fp8x2_to_bf16x2(t.v[u].w, true);
-      *reinterpret_cast<u32x4*>(vtile + v_lds_addr(r, c)) = lo;
-      *reinterpret_cast<u32x4*>(vtile + v_lds_addr(r, c + 1)) = hi;
+      widen_fp8x16(regs[u], lo, hi);
+      *reinterpret_cast<u32x4*>(tile + (IS_V ? v_lds_addr(r, c) : k_lds_addr(r, c))) = lo;
+      *reinterpret_cast<u32x4*>(tile + (IS_V ? v_lds_addr(r, c + 1) : k_lds_addr(r, c + 1))) = hi;
     }
   }
+}
+
+template <bool FP8>
+__device__ __forceinline__ void tile_to_lds(const TileRegs<FP8>& t, uint8_t* ktile, uint8_t* vtile, int lane) {
+  rows_to_lds<FP8, false>(t.k, ktile, lane);
+  rows_to_lds<FP8, true>(t.v, vtile, lane);
 }
 
 // S^T of the tile: acc[sub][rb] (sub = 16-token half, rb = 16-row block of Q).
@@ -126,35 +132,28 @@ __device__ __forceinline__ void tile_qk(const uint8_t* ktile, const bf16x8 (&qf)
 
 // O^T += V^T P^T for the tile.  p[rb] is lane (n, g)'s B operand: elements
 // 0..3 = P[row n][token 4g+0..3], elements 4..7 = P[row n][token 16+4g+0..3].
-// The V^T operand is built from 8-byte LDS reads (4 dims of one token) and an
-// in-register 8x4 transpose, so lane m of dim block (half h, e) carries dim
-// 64h + 4m + e; the accumulator o[rb][4h+e] element i of lane (n, g) is
-// therefore O[row n][64h + 16g + 4i + e].
+// The V^T operand comes from ds_read_b64_tr_b16: within each group of 16
+// lanes, lane 4k+a supplies the address of 4 dims (16db+4a..+3) of token k of
+// the group, and lane m receives dim 16db+m of the four tokens.  The
+// accumulator o[rb][db] element i of lane (n, g) is O[row n][16db + 4g + i].
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+
 template <int RB>
 __device__ __forceinline__ void tile_pv(const uint8_t* vtile, const bf16x8 (&p)[RB], f32x4 (&o)[RB][8], int lane) {
-  const int m = lane & 15, g = lane >> 4;
+  const int j = lane & 15, g = lane >> 4;
+  const int k = j >> 2, a = j & 3;
+  const int row0 = 4 * g + k, row1 = 16 + 4 * g + k;
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    u32x2 w[8];
+  for (int db = 0; db < 8; ++db) {
+    const int c = 2 * db + (a >> 1);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vtile + v_lds_addr(row0, c) + (a & 1) * 8));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vtile + v_lds_addr(row1, c) + (a & 1) * 8));
+    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    const bf16x8 av = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int tok = (j < 4) ? (4 * g + j) : (16 + 4 * g + (j - 4));
-      w[j] = *reinterpret_cast<const u32x2*>(vtile + v_lds_addr(tok, 8 * h + (m >> 1)) + (m & 1) * 8);
-    }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      u32x4 a;
-      const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-#pragma unroll
-      for (int pr = 0; pr < 4; ++pr) {
-        const uint32_t lo = (e & 2) ? w[2 * pr].y : w[2 * pr].x;
-        const uint32_t hi = (e & 2) ? w[2 * pr + 1].y : w[2 * pr + 1].x;
-        a[pr] = __builtin_amdgcn_perm(hi, lo, sel);
-      }
-      const bf16x8 av = as_bf16x8(a);
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) o[rb][4 * h + e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, p[rb], o[rb][4 * h + e], 0, 0, 0);
-    }
+    for (int rb = 0; rb < RB; ++rb) o[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, p[rb], o[rb][db], 0, 0, 0);
   }
 }
 

@@ -156,6 +156,8 @@ size_t pillar_workspace_bytes(const pillar_kv_t* kv, int32_t spec_len_k, int32_t
   if (check_kv(kv) != PILLAR_OK || check_spec(kv, spec_len_k) != PILLAR_OK || max_budget < 0) return 0;
   const KvView v = make_view(kv);
   size_t need = verify_workspace(v, spec_len_k + 1);
+  const size_t dec = (v.head_dim == 128) ? decode_mfma_workspace(v, max_budget) : 0;
+  if (dec > need) need = dec;
   return need < 256 ? 256 : need;
 }
 
@@ -218,8 +220,6 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
   if (rc != PILLAR_OK) return rc;
   if (!q || !indices || !counts || !out) return PILLAR_EINVAL;
   if (max_budget < 1) return PILLAR_EINVAL;
-  (void)workspace;
-  (void)workspace_bytes;
   DecodeArgs a;
   a.kv = make_view(kv);
   a.q = q;
@@ -231,8 +231,13 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
   a.q_dtype = kv->q_dtype;
   a.kv_dtype = kv->kv_dtype;
   a.workspace = workspace;
-  const hipError_t e = launch_decode_generic(a, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+  const hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (!force_generic() && decode_mfma_supported(a)) {
+    rc = check_workspace(workspace, workspace_bytes, decode_mfma_workspace(a.kv, max_budget));
+    if (rc != PILLAR_OK) return rc;
+    return launch_decode_mfma(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+  }
+  return launch_decode_generic(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
 }
 
 void pillar_profile_enable(int on) {

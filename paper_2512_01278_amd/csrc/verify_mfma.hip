@@ -319,14 +319,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_split_mfma(KvView kv, cons
         if (r < R) {
           float* dst = ws.part_o + (static_cast<int64_t>(id) * R + r) * kHeadDim;
 #pragma unroll
-          for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              f32x4 v;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] = o[rb][4 * h + e][i];
-              *reinterpret_cast<f32x4*>(dst + 64 * h + 16 * g4 + 4 * i) = v;
-            }
+          for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + 16 * db + 4 * g4) = o[rb][db];
         }
       }
     }
