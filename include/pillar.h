@@ -156,6 +156,14 @@ void pillar_profile_enable(int on);
 void pillar_profile_reset(void);
 int  pillar_profile_read(pillar_kernel_time* entries, int cap);
 
+/* Tuning knobs for benchmarking (process-wide, not thread-safe against
+ * running calls).  Known names: "verify_chunk" (tokens per verification work
+ * item, multiple of 128), "verify_grid" (persistent workgroups per compute
+ * unit), "decode_wgs" (workgroup count the draft kernel aims for).  A value
+ * of 0 restores the default.  Returns PILLAR_EINVAL for an unknown name or a
+ * value outside the knob's range. */
+int pillar_set_option(const char* name, int64_t value);
+
 #ifdef __cplusplus
 }
 #endif

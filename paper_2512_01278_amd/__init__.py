@@ -8,8 +8,8 @@ from . import binding
 from .binding import (KvCache, DeviceWorkload, PillarError, upload_workload, pillar_version,
                       pillar_workspace_bytes, pillar_verify_attn, pillar_select_topk,
                       pillar_sparse_decode, pillar_profile_enable, pillar_profile_reset,
-                      pillar_profile_read, status_string)
+                      pillar_profile_read, pillar_set_option, status_string)
 
 __all__ = ["binding", "KvCache", "DeviceWorkload", "PillarError", "upload_workload", "pillar_version",
            "pillar_workspace_bytes", "pillar_verify_attn", "pillar_select_topk", "pillar_sparse_decode",
-           "pillar_profile_enable", "pillar_profile_reset", "pillar_profile_read", "status_string"]
+           "pillar_profile_enable", "pillar_profile_reset", "pillar_profile_read", "pillar_set_option", "status_string"]

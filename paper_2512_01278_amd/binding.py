@@ -23,7 +23,7 @@ DTYPE_CODE = {"f32": PILLAR_F32, "bf16": PILLAR_BF16, "fp8_e4m3": PILLAR_FP8_E4M
 
 EXPORTS = ("pillar_version", "pillar_status_string", "pillar_workspace_bytes", "pillar_verify_attn",
            "pillar_select_topk", "pillar_sparse_decode", "pillar_profile_enable", "pillar_profile_reset",
-           "pillar_profile_read")
+           "pillar_profile_read", "pillar_set_option")
 
 
 class pillar_kv_t(C.Structure):
@@ -77,6 +77,8 @@ def load() -> C.CDLL:
     lib.pillar_sparse_decode.restype = C.c_int
     lib.pillar_sparse_decode.argtypes = [C.POINTER(pillar_kv_t), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.pillar_set_option.restype = C.c_int
+    lib.pillar_set_option.argtypes = [C.c_char_p, C.c_int64]
     lib.pillar_profile_enable.restype = None
     lib.pillar_profile_enable.argtypes = [C.c_int]
     lib.pillar_profile_reset.restype = None
@@ -184,6 +186,10 @@ def pillar_sparse_decode(kv: KvCache, q: torch.Tensor, indices: torch.Tensor, co
     rc = load().pillar_sparse_decode(C.byref(s), q.data_ptr(), indices.data_ptr(), counts.data_ptr(), max_budget,
                                      out.data_ptr(), _ptr(lse), _ptr(workspace), wsz, _stream(stream))
     _check(rc, "pillar_sparse_decode")
+
+
+def pillar_set_option(name: str, value: int) -> None:
+    _check(load().pillar_set_option(name.encode(), int(value)), f"pillar_set_option({name})")
 
 
 def pillar_profile_enable(on: bool) -> None:

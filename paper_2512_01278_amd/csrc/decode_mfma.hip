@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_split_mfma(DecodeArgs a, D
   const int ntiles = (j_end - j_begin + kTileTokens - 1) / kTileTokens;
   const int32_t* list = a.indices + (static_cast<int64_t>(b) * kv.num_kv_heads + g) * a.max_budget;
   uint8_t* ktile = smem + wave * kWaveLds;
-  uint8_t* vtile = ktile + kTileBytes;
+  uint8_t* vtile = ktile + kKTileBytes;
   const float c2 = kv.sm_scale * kLog2e;
 
   f32x4 o[1][8];

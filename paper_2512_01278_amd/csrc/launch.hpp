@@ -64,11 +64,24 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
 bool verify_mfma_supported(const VerifyArgs& a);
 size_t verify_mfma_workspace(const KvView& kv, int n_q);
 hipError_t launch_verify_mfma(const VerifyArgs& a, hipStream_t s);
+bool verify_fused_supported(const VerifyArgs& a);      // needs a.scores
+size_t verify_fused_workspace(const KvView& kv, int n_q);
+size_t verify_fused_trace_offset(const KvView& kv, int n_q);
+hipError_t launch_verify_fused(const VerifyArgs& a, hipStream_t s);
 bool decode_mfma_supported(const DecodeArgs& a);
 size_t decode_mfma_workspace(const KvView& kv, int max_budget);
 hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s);
 
 // true when the environment asks for the generic kernels everywhere
 bool force_generic();
+
+// process-wide tuning knobs (pillar_set_option); 0 = default
+struct Options {
+  int verify_chunk = 0;
+  int verify_grid = 0;
+  int decode_wgs = 0;
+  int debug = 0;      // experiment switches, meaning private to the kernels
+};
+Options& options();
 
 }  // namespace pillar

@@ -18,9 +18,9 @@
 // is already the B-operand layout of P^T once the contraction index is
 // permuted, which costs nothing because V^T is read with the same permutation.
 //
-// LDS layout of a tile: 32 rows of 256 B, 16-byte chunks XOR-swizzled per row
-// so that the column-wise MFMA operand reads (K) and the transposing reads (V)
-// spread over all banks.
+// LDS layout of a tile: 32 padded rows (see kKRow / kVRow) so that the
+// column-wise MFMA operand reads (K) and the transposing reads (V) spread over
+// all banks.
 #pragma once
 
 #include "common.hpp"
@@ -34,14 +34,23 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kTileTokens = 32;
 constexpr int kHeadDim = 128;
-constexpr int kTileBytes = kTileTokens * kHeadDim * 2;   // one K or V tile in LDS (bf16)
-constexpr int kWaveLds = 2 * kTileBytes;                 // K tile + V tile
+// LDS rows are padded instead of swizzled: every access of a lane is then
+// "per-lane base + compile-time offset", one address register per access kind.
+//   K rows, 272 B apart: the 16 lanes of an MFMA operand read (16 rows, one
+//   16-byte chunk each) fall 4 banks apart -> all 64 banks, no conflict.
+//   V rows, 288 B apart: the 16 lanes of a transposing read (4 rows x 32 B)
+//   fall 8 banks apart per row, and the next lane group 32 banks further.
+constexpr int kKRow = 272;
+constexpr int kVRow = 288;
+constexpr int kKTileBytes = kTileTokens * kKRow;         // 8704
+constexpr int kVTileBytes = kTileTokens * kVRow;         // 9216
+constexpr int kWaveLds = kKTileBytes + kVTileBytes;      // K tile + V tile of one wavefront
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // byte address of 16-byte chunk `c` of row `r` in a K tile / a V tile
-__device__ __forceinline__ int k_lds_addr(int r, int c) { return r * 256 + ((c ^ (r & 15)) << 4); }
-__device__ __forceinline__ int v_lds_addr(int r, int c) { return r * 256 + ((c ^ (((r & 3) << 1) | (((r >> 2) & 1) << 3))) << 4); }
+__device__ __forceinline__ int k_lds_addr(int r, int c) { return r * kKRow + (c << 4); }
+__device__ __forceinline__ int v_lds_addr(int r, int c) { return r * kVRow + (c << 4); }
 
 __device__ __forceinline__ float xor16(float v) { return __shfl_xor(v, 16, 64); }
 __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
@@ -154,6 +163,7 @@ __device__ __forceinline__ void tile_pv(const uint8_t* vtile, const bf16x8 (&p)[
     const bf16x8 av = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) o[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, p[rb], o[rb][db], 0, 0, 0);
+    if (RB > 1 && (db & 1)) __builtin_amdgcn_sched_barrier(0);     // keeps the operand reads from piling up in registers
   }
 }
 

@@ -120,11 +120,21 @@ int check_workspace(const void* ws, size_t have, size_t need) {
 
 size_t verify_workspace(const KvView& v, int n_q) {
   const size_t a = verify_generic_workspace(v, n_q);
-  const size_t b = (v.head_dim == 128 && v.page_size >= 16) ? verify_mfma_workspace(v, n_q) : 0;
+  size_t b = 0;
+  if (v.head_dim == 128 && v.page_size >= 16) {
+    b = verify_mfma_workspace(v, n_q);
+    const size_t c = verify_fused_workspace(v, n_q);
+    if (c > b) b = c;
+  }
   return a > b ? a : b;
 }
 
 }  // namespace
+
+Options& options() {
+  static Options o;
+  return o;
+}
 
 bool force_generic() {
   static const bool on = [] {
@@ -184,8 +194,10 @@ int pillar_verify_attn(const pillar_kv_t* kv, const void* q, int32_t spec_len_k,
   rc = check_workspace(workspace, workspace_bytes, verify_workspace(a.kv, a.n_q));
   if (rc != PILLAR_OK) return rc;
   const hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const hipError_t e = (!force_generic() && verify_mfma_supported(a)) ? launch_verify_mfma(a, st)
-                                                                       : launch_verify_generic(a, st);
+  hipError_t e;
+  if (!force_generic() && verify_fused_supported(a)) e = launch_verify_fused(a, st);
+  else if (!force_generic() && verify_mfma_supported(a)) e = launch_verify_mfma(a, st);
+  else e = launch_verify_generic(a, st);
   return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
 }
 
@@ -238,6 +250,33 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
     return launch_decode_mfma(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
   }
   return launch_decode_generic(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+}
+
+int pillar_set_option(const char* name, int64_t value) {
+  if (!name || value < 0) return PILLAR_EINVAL;
+  Options& o = options();
+  const std::string k(name);
+  if (k == "verify_chunk") {
+    if (value % 128 != 0 || value > 65536) return PILLAR_EINVAL;
+    o.verify_chunk = static_cast<int>(value);
+  } else if (k == "verify_grid") {
+    if (value > 8) return PILLAR_EINVAL;
+    o.verify_grid = static_cast<int>(value);
+  } else if (k == "decode_wgs") {
+    if (value > (1 << 20)) return PILLAR_EINVAL;
+    o.decode_wgs = static_cast<int>(value);
+  } else if (k == "debug") {
+    o.debug = static_cast<int>(value);
+  } else {
+    return PILLAR_EINVAL;
+  }
+  return PILLAR_OK;
+}
+
+// debugging aid (not part of the documented ABI): byte offset of the timestamp trace in the workspace
+size_t pillar_debug_trace_offset(const pillar_kv_t* kv, int32_t spec_len_k) {
+  if (check_kv(kv) != PILLAR_OK) return 0;
+  return verify_fused_trace_offset(make_view(kv), spec_len_k + 1);
 }
 
 void pillar_profile_enable(int on) {

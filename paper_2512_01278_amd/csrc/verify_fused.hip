@@ -1,0 +1,834 @@
+// Verification attention with the score statistic, in one persistent kernel
+// (bf16 queries, bf16 or fp8 KV, head_dim 128, pages of >= 16 tokens).
+//
+// Paper Section 4.1: the verification pass yields, besides its output, the
+// softmax probabilities of the k+1 verification rows, averaged over rows and
+// over the query heads of one GQA group; Top-K reads that statistic next.  A
+// probability needs the row's log-sum-exp over the WHOLE context, which is
+// only known once every token has been seen.  The paper caches logits and
+// log-sum-exp and rematerialises; here the logits are recomputed instead,
+// because re-reading K is nearly free on this chip when it happens soon after
+// the first read: the Infinity Cache (256 MB, memory side) serves the second
+// read at HBM-like bandwidth ON TOP of what HBM delivers (measured: streaming
+// 2 GB while re-reading data touched 64 MB earlier costs about 10 % more time
+// than streaming alone).  A logit dump would add 16..60 % HBM traffic.
+//
+// Each (request, KV head) is cut into slices of `slice_tokens` tokens.  A
+// slice is visited twice by the same workgroup:
+//   phase 1  K only: S^T = K Q^T on the matrix cores, running (max, sum) per
+//            row -> the slice's (m, l).  The last slice of a pair to finish
+//            combines all (m, l) of the pair into the final log-sum-exp.
+//   phase 2  K (from the Infinity Cache) and V: p = exp2(s - lse) is the exact
+//            probability, so the score statistic is written directly, and
+//            O = sum p V needs no running maximum and no rescaling; slice
+//            partials of O add linearly and the last slice to finish sums them.
+// A workgroup interleaves the two: phase 1 of its next slice, then phase 2 of
+// the previous one, so that the pair of the previous slice has normally been
+// completed by the other workgroups in the meantime and nobody waits.
+//
+// Progress: slices are handed out by one atomic ticket in pair-major order; a
+// workgroup waits (phase 2) only for slices whose tickets were handed out, and
+// a workgroup holding a ticket never waits before its phase 1 is published.
+// Every workgroup can hold two slices, so a pair completes as long as it has at
+// most 2 x (resident workgroups) slices; the host only selects this kernel
+// below that bound, and the wait is a bounded spin that counts a timeout in
+// the workspace instead of hanging.
+#include "launch.hpp"
+#include "mfma_tile.hpp"
+
+namespace pillar {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+constexpr int kLdsBytes = kWaves * kWaveLds;
+constexpr int kSpinLimit = 1 << 20;
+constexpr int kDefaultSlice = 512;
+constexpr int kMaxBatchInLds = 4096;
+
+struct FusedWs {
+  int32_t* ctrl;        // [0] ticket  [1] slice count  [2] timeouts
+  int32_t* slice_base;  // [B+1] first slice of request b; its slices are head-major
+  int32_t* slices;      // [max_slices][4] = {b, g, c, L}
+  int32_t* cnt1;        // [pairs] slices that finished phase 1
+  int32_t* cnt2;        // [pairs] slices that finished phase 2
+  int32_t* ready;       // [pairs] 1 once lse2 of the pair is final
+  float* part_m;        // [max_slices][RB*16]  log2 domain
+  float* part_l;        // [max_slices][RB*16]
+  float* part_o;        // [max_slices][R][128]
+  float* lse2;          // [pairs][RB*16]       log2 domain
+  int32_t slice_tokens;
+  int32_t max_slices;
+  int32_t debug;
+  long long* trace;     // [8192] timestamps of workgroup 0 when debug bit 16 is set
+};
+
+__host__ __device__ inline int slices_of(int len, int slice_tokens) { return (len + slice_tokens - 1) / slice_tokens; }
+
+// ---------------------------------------------------------------- plan ------
+__global__ __launch_bounds__(1024) void fused_plan(KvView kv, FusedWs ws) {
+  __shared__ int32_t base[kMaxBatchInLds + 1];
+  __shared__ int32_t scan[1024];
+  __shared__ int32_t carry;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  for (int b0 = 0; b0 < kv.batch; b0 += 1024) {
+    const int b = b0 + threadIdx.x;
+    const int mine = b < kv.batch ? slices_of(kv.seq_lens[b], ws.slice_tokens) * kv.num_kv_heads : 0;
+    scan[threadIdx.x] = mine;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      const int v = threadIdx.x >= o ? scan[threadIdx.x - o] : 0;
+      __syncthreads();
+      scan[threadIdx.x] += v;
+      __syncthreads();
+    }
+    if (b < kv.batch) base[b] = carry + scan[threadIdx.x] - mine;
+    __syncthreads();
+    if (threadIdx.x == 1023) carry += scan[1023];
+    __syncthreads();
+  }
+  const int total = carry;
+  if (threadIdx.x == 0) base[kv.batch] = total;
+  __syncthreads();
+  for (int b = threadIdx.x; b <= kv.batch; b += 1024) ws.slice_base[b] = base[b];
+  for (int j = threadIdx.x; j < total; j += 1024) {
+    int lo = 0, hi = kv.batch - 1;            // last b with base[b] <= j
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (base[mid] <= j) lo = mid; else hi = mid - 1;
+    }
+    const int L = kv.seq_lens[lo];
+    const int ns = slices_of(L, ws.slice_tokens);
+    const int rel = j - base[lo];
+    int4 e;
+    e.x = lo;
+    e.y = rel / ns;
+    e.z = rel - e.y * ns;
+    e.w = L;
+    reinterpret_cast<int4*>(ws.slices)[j] = e;
+  }
+  const int pairs = kv.batch * kv.num_kv_heads;
+  for (int p = threadIdx.x; p < pairs; p += 1024) {
+    ws.cnt1[p] = 0;
+    ws.cnt2[p] = 0;
+    ws.ready[p] = 0;
+  }
+  if (threadIdx.x == 0) {
+    ws.ctrl[0] = 0;
+    ws.ctrl[1] = total;
+    ws.ctrl[2] = 0;
+  }
+}
+
+// ------------------------------------------------------------- helpers ------
+struct Slice {
+  int id, b, g, c, L, t_begin, t_end, nslices, first, pair;
+};
+
+__device__ __forceinline__ Slice decode_slice(const KvView& kv, const FusedWs& ws, int id) {
+  const int4 e = reinterpret_cast<const int4*>(ws.slices)[id];
+  Slice s;                                  // the same for every lane: keep it in scalar registers
+  s.id = __builtin_amdgcn_readfirstlane(id);
+  s.b = __builtin_amdgcn_readfirstlane(e.x);
+  s.g = __builtin_amdgcn_readfirstlane(e.y);
+  s.c = __builtin_amdgcn_readfirstlane(e.z);
+  s.L = __builtin_amdgcn_readfirstlane(e.w);
+  s.t_begin = s.c * ws.slice_tokens;
+  s.t_end = min(s.L, s.t_begin + ws.slice_tokens);
+  s.nslices = slices_of(s.L, ws.slice_tokens);
+  s.first = id - s.c;                       // slice 0 of this (request, head)
+  s.pair = s.b * kv.num_kv_heads + s.g;
+  return s;
+}
+
+template <int RB>
+__device__ __forceinline__ void load_q(const KvView& kv, const uint16_t* q, int n_q, int G, int R, const Slice& it,
+                                       bf16x8 (&qf)[RB][4], int lane) {
+  const int n = lane & 15, g4 = lane >> 4;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int r = 16 * rb + n;
+    const int i = r / G, hg = r - i * G;
+    const uint16_t* row = q + ((static_cast<int64_t>(it.b) * n_q + i) * kv.num_q_heads + it.g * G + hg) * kHeadDim;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (r < R) v = *reinterpret_cast<const u32x4*>(row + 32 * s + 8 * g4);
+      qf[rb][s] = as_bf16x8(v);
+    }
+  }
+}
+
+__device__ __forceinline__ int load_pages(const KvView& kv, const Slice& it, int lane) {
+  const int first_page = it.t_begin >> kv.page_shift;
+  const int last_page = (it.L - 1) >> kv.page_shift;
+  return kv.block_table[static_cast<int64_t>(it.b) * kv.block_table_stride + min(first_page + lane, last_page)];
+}
+
+// Per-lane constants of the row-coalesced tile loads.
+template <bool FP8> struct LaneGeom {
+  uint32_t lane_off;   // byte offset of this lane's row (within a 16-token group) and column
+  uint32_t row_step;   // bytes between the rows two consecutive loads of a lane cover
+  int row;             // this lane's row within the tile for load 0
+};
+
+template <bool FP8>
+__device__ __forceinline__ LaneGeom<FP8> lane_geom(const KvView& kv, int lane) {
+  constexpr int kLanesPerRow = FP8 ? 8 : 16;
+  const int esz = FP8 ? 1 : 2;
+  LaneGeom<FP8> g;
+  g.row = lane / kLanesPerRow;
+  g.lane_off = static_cast<uint32_t>(g.row * kv.stride_slot * esz + (lane % kLanesPerRow) * 16);
+  g.row_step = static_cast<uint32_t>((64 / kLanesPerRow) * kv.stride_slot * esz);
+  return g;
+}
+
+// Issues the loads of the tile at token tb: K rows into rk, and V rows into rv
+// when WITH_V.  A 16-token group lies in one page whose id is wave-uniform, so
+// the address is a scalar base per group plus a 32-bit per-lane offset.  Groups
+// (or rows) beyond the end of the sequence read the last page of the request:
+// pages are whole, so the rows exist; the caller masks them.
+template <bool FP8, bool WITH_V>
+__device__ __forceinline__ void issue_rows(const KvView& kv, const Slice& it, int tb, int pg, const LaneGeom<FP8>& geo,
+                                           u32x4 (&rk)[TileRegs<FP8>::kLoads], u32x4 (&rv)[TileRegs<FP8>::kLoads], int lane) {
+  constexpr int kLoads = TileRegs<FP8>::kLoads;
+  constexpr int kPerGroup = kLoads / 2;
+  const int esz = FP8 ? 1 : 2;
+  const int first_page = it.t_begin >> kv.page_shift;
+  const int last_page = (it.L - 1) >> kv.page_shift;
+#pragma unroll
+  for (int grp = 0; grp < 2; ++grp) {
+    const int tok0 = tb + 16 * grp;
+    const int page = __builtin_amdgcn_readlane(pg, min(tok0 >> kv.page_shift, last_page) - first_page);
+    const int64_t base = (static_cast<int64_t>(page) * kv.stride_page + static_cast<int64_t>(it.g) * kv.stride_head +
+                          static_cast<int64_t>(tok0 & (kv.page_size - 1)) * kv.stride_slot) * esz;
+    const char* gk = static_cast<const char*>(kv.k_pool) + base;
+    const char* gv = static_cast<const char*>(kv.v_pool) + base;
+#pragma unroll
+    for (int u = 0; u < kPerGroup; ++u) {
+      const uint32_t off = geo.lane_off + u * geo.row_step;
+      rk[grp * kPerGroup + u] = *reinterpret_cast<const u32x4*>(gk + off);
+      if constexpr (WITH_V) rv[grp * kPerGroup + u] = *reinterpret_cast<const u32x4*>(gv + off);
+    }
+  }
+}
+
+// One tile fetch described by scalars, so that a loop needs a single load site
+// whatever slice and phase the next tile belongs to.
+struct Fetch {
+  int g, first_page, last_page, tb, pg;
+  bool with_v, valid;
+};
+
+__device__ __forceinline__ Fetch fetch_of(const KvView& kv, const Slice& s, int pg, int tile, bool with_v, bool valid) {
+  Fetch f;
+  f.g = s.g;
+  f.first_page = s.t_begin >> kv.page_shift;
+  f.last_page = (s.L - 1) >> kv.page_shift;
+  f.tb = s.t_begin + tile * kTileTokens;
+  f.pg = pg;
+  f.with_v = with_v;
+  f.valid = valid;
+  return f;
+}
+
+__device__ __forceinline__ Fetch pick(bool c, const Fetch& a, const Fetch& b) {
+  Fetch f;
+  f.g = c ? a.g : b.g;
+  f.first_page = c ? a.first_page : b.first_page;
+  f.last_page = c ? a.last_page : b.last_page;
+  f.tb = c ? a.tb : b.tb;
+  f.pg = c ? a.pg : b.pg;
+  f.with_v = c ? a.with_v : b.with_v;
+  f.valid = c ? a.valid : b.valid;
+  return f;
+}
+
+template <bool FP8>
+__device__ __forceinline__ void issue_fetch(const KvView& kv, const Fetch& f, const LaneGeom<FP8>& geo,
+                                            u32x4 (&rk)[TileRegs<FP8>::kLoads], u32x4 (&rv)[TileRegs<FP8>::kLoads]) {
+  if (!f.valid) return;
+  constexpr int kLoads = TileRegs<FP8>::kLoads;
+  constexpr int kPerGroup = kLoads / 2;
+  const int esz = FP8 ? 1 : 2;
+#pragma unroll
+  for (int grp = 0; grp < 2; ++grp) {
+    const int tok0 = f.tb + 16 * grp;
+    const int page = __builtin_amdgcn_readlane(f.pg, min(tok0 >> kv.page_shift, f.last_page) - f.first_page);
+    const int64_t base = (static_cast<int64_t>(page) * kv.stride_page + static_cast<int64_t>(f.g) * kv.stride_head +
+                          static_cast<int64_t>(tok0 & (kv.page_size - 1)) * kv.stride_slot) * esz;
+    const char* gk = static_cast<const char*>(kv.k_pool) + base;
+    const char* gv = static_cast<const char*>(kv.v_pool) + base;
+#pragma unroll
+    for (int u = 0; u < kPerGroup; ++u) rk[grp * kPerGroup + u] = *reinterpret_cast<const u32x4*>(gk + (geo.lane_off + u * geo.row_step));
+    if (f.with_v) {
+#pragma unroll
+      for (int u = 0; u < kPerGroup; ++u) rv[grp * kPerGroup + u] = *reinterpret_cast<const u32x4*>(gv + (geo.lane_off + u * geo.row_step));
+    }
+  }
+}
+
+// Rows of the tile that lie beyond the sequence hold whatever the page holds;
+// V must not bring NaN into the matrix product (0 * NaN), so they are zeroed.
+template <bool FP8>
+__device__ __forceinline__ void zero_tail_rows(u32x4 (&rv)[TileRegs<FP8>::kLoads], int tb, int L, const LaneGeom<FP8>& geo) {
+  constexpr int kRowsPerLoad = FP8 ? 8 : 4;
+#pragma unroll
+  for (int u = 0; u < TileRegs<FP8>::kLoads; ++u)
+    if (tb + kRowsPerLoad * u + geo.row >= L) rv[u] = u32x4{0u, 0u, 0u, 0u};
+}
+
+// fp8: dequantisation scales of the two 16-token halves of a tile
+__device__ __forceinline__ void half_scales(const KvView& kv, const Slice& it, int tb, int pg, const float* table, float (&sc)[2]) {
+  const int first_page = it.t_begin >> kv.page_shift;
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) {
+    const int tok = min(tb + 16 * sub, it.L - 1);
+    const int page = __builtin_amdgcn_readlane(pg, (tok >> kv.page_shift) - first_page);
+    sc[sub] = table[static_cast<int64_t>(page) * kv.num_kv_heads + it.g];
+  }
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v;
+  v[0] = static_cast<__bf16>(a);
+  v[1] = static_cast<__bf16>(b);
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// ---------------------------------------------------------------- kernel ----
+// stores that other workgroups (possibly on another XCD, behind another L2)
+// will read: written through to memory, so that publishing them needs no L2
+// write-back, only a wait for the acknowledgements
+__device__ __forceinline__ void publish(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void publish4(float* p, const f32x4& v) {
+  publish(p, v.x); publish(p + 1, v.y); publish(p + 2, v.z); publish(p + 3, v.w);
+}
+// eight 16-byte write-through stores (dims 16db + 4g .. +3 of one row) and the wait for their acknowledgement
+__device__ __forceinline__ void publish_row(float* p, const f32x4 (&v)[8]) {
+  asm volatile(
+      "global_store_dwordx4 %0, %1, off sc1\n\t"
+      "global_store_dwordx4 %0, %2, off offset:64 sc1\n\t"
+      "global_store_dwordx4 %0, %3, off offset:128 sc1\n\t"
+      "global_store_dwordx4 %0, %4, off offset:192 sc1\n\t"
+      "global_store_dwordx4 %0, %5, off offset:256 sc1\n\t"
+      "global_store_dwordx4 %0, %6, off offset:320 sc1\n\t"
+      "global_store_dwordx4 %0, %7, off offset:384 sc1\n\t"
+      "global_store_dwordx4 %0, %8, off offset:448 sc1\n\t"
+      "s_waitcnt vmcnt(0)"
+      :
+      : "v"(p), "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "v"(v[4]), "v"(v[5]), "v"(v[6]), "v"(v[7])
+      : "memory");
+}
+__device__ __forceinline__ float peek(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void wait_stores() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+
+__device__ __forceinline__ int tiles_of(const Slice& s) { return (s.t_end - s.t_begin + kTileTokens - 1) / kTileTokens; }
+
+// S^T of the tile with the Q operand read from LDS (rows in K-tile layout)
+template <int RB>
+__device__ __forceinline__ void tile_qk_ldsq(const uint8_t* ktile, const uint8_t* qtile, int R, f32x4 (&acc)[2][RB], int lane) {
+  const int n = lane & 15, g = lane >> 4;
+  int qrow[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) qrow[rb] = min(16 * rb + n, R);
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[sub][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const bf16x8 a0 = as_bf16x8(*reinterpret_cast<const u32x4*>(ktile + k_lds_addr(n, 4 * s + g)));
+    const bf16x8 a1 = as_bf16x8(*reinterpret_cast<const u32x4*>(ktile + k_lds_addr(16 + n, 4 * s + g)));
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const bf16x8 b = as_bf16x8(*reinterpret_cast<const u32x4*>(qtile + k_lds_addr(qrow[rb], 4 * s + g)));
+      acc[0][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc[0][rb], 0, 0, 0);
+      acc[1][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc[1][rb], 0, 0, 0);
+    }
+    if (RB > 1) __builtin_amdgcn_sched_barrier(0);     // keeps the operand reads from piling up in registers
+  }
+}
+
+#ifdef PILLAR_TRACING
+#define PILLAR_TRACE(tag) do { if ((ws.debug & 16) && blockIdx.x == 0 && threadIdx.x == 0 && tr_n < 8190) { ws.trace[tr_n++] = (static_cast<long long>(tag) << 48) | (wall_clock64() & 0xffffffffffffll); } } while (0)
+#else
+#define PILLAR_TRACE(tag) do { } while (0)
+#endif
+
+template <int RB, bool FP8>
+__global__ __launch_bounds__(kThreads, 2) void verify_fused_mfma(KvView kv, const uint16_t* q, int n_q, FusedWs ws,
+                                                                 uint16_t* out, float* lse_out, float* scores,
+                                                                 int64_t score_stride) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  __shared__ int s_ticket[2], s_flag;
+  __shared__ float s_m[kWaves][RB * 16], s_l[kWaves][RB * 16];
+  // Q rows of the phase-2 slice in K-tile layout: rows 0..R-1, then one row of zeros that
+  // stands in for every padded row of the last 16-row block
+  __shared__ __attribute__((aligned(16))) uint8_t s_q[(RB * 16 + 1) * kKRow];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = lane & 15, g4 = lane >> 4;
+  uint8_t* ktile = smem + wave * kWaveLds;
+  uint8_t* vtile = ktile + kKTileBytes;
+  const int G = kv.num_q_heads / kv.num_kv_heads;
+  const int R = n_q * G;
+  const float c2 = kv.sm_scale * kLog2e;
+  const float inv_r = 1.0f / static_cast<float>(R);
+  const int total = ws.ctrl[1];
+  const LaneGeom<FP8> geo = lane_geom<FP8>(kv, lane);
+  constexpr int kLoads = TileRegs<FP8>::kLoads;
+
+  // registers of the tile in flight: the last tile of a phase already fetches
+  // the first tile of the next phase, so they live across phases
+  u32x4 rk[kLoads], rv[kLoads];
+  Slice nxt = {}, pnd = {};
+  int nxt_pg = 0, pnd_pg = 0;
+  bool has_nxt = false, has_pnd = false;
+  bool k_ahead = false;            // rk holds this wave's first K tile of `nxt`
+  bool kv_ahead = false;           // rk, rv hold this wave's first tile of `pnd`
+  int parity = 0;
+  [[maybe_unused]] int tr_n = 1;
+
+  if (threadIdx.x == 0) s_ticket[0] = atomicAdd(&ws.ctrl[0], 1);
+  __syncthreads();
+  if (s_ticket[0] < total) {
+    has_nxt = true;
+    nxt = decode_slice(kv, ws, s_ticket[0]);
+    nxt_pg = load_pages(kv, nxt, lane);
+  }
+
+  while (has_nxt || has_pnd) {
+    const Slice cur = nxt;
+    const int cur_pg = nxt_pg;
+    const bool has_cur = has_nxt;
+    const int nt_pnd = has_pnd ? tiles_of(pnd) : 0;
+    parity ^= 1;
+    if (has_cur && threadIdx.x == 0) s_ticket[parity] = atomicAdd(&ws.ctrl[0], 1);   // read after the next barrier
+    has_nxt = false;
+
+    PILLAR_TRACE(1);
+    // Q rows of the slice whose phase 2 follows: global -> LDS while phase 1 runs
+    if (has_pnd) {
+      for (int ch = threadIdx.x; ch < (R + 1) * 16; ch += kThreads) {
+        const int r = ch >> 4, c = ch & 15;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (r < R) {
+          const int i = r / G, hg = r - i * G;
+          v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(pnd.b) * n_q + i) * kv.num_q_heads + pnd.g * G + hg) * kHeadDim + 8 * c);
+        }
+        *reinterpret_cast<u32x4*>(s_q + k_lds_addr(r, c)) = v;
+      }
+    }
+
+    // =================== phase 1: K only -> (m, l) of the slice ===================
+    if (has_cur) {
+      const int nt = tiles_of(cur);
+      float m_run[RB], l_run[RB];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) { m_run[rb] = -INFINITY; l_run[rb] = 0.f; }
+      if (wave < nt) {
+        bf16x8 qf[RB][4];
+        load_q<RB>(kv, q, n_q, G, R, cur, qf, lane);
+        const int pg = cur_pg;
+        if (!k_ahead) issue_fetch<FP8>(kv, fetch_of(kv, cur, pg, wave, false, true), geo, rk, rv);
+        const Fetch after = fetch_of(kv, pnd, pnd_pg, wave, true, wave < nt_pnd);   // first tile of phase 2
+        for (int ti = wave; ti < nt; ti += kWaves) {
+          const int tb = cur.t_begin + ti * kTileTokens;
+          PILLAR_TRACE(10);
+          rows_to_lds<FP8, false>(rk, ktile, lane);
+          PILLAR_TRACE(11);
+          float ks[2] = {1.f, 1.f};
+          if constexpr (FP8) half_scales(kv, cur, tb, pg, kv.k_scale, ks);
+          issue_fetch<FP8>(kv, pick(ti + kWaves < nt, fetch_of(kv, cur, pg, ti + kWaves, false, true), after), geo, rk, rv);
+          f32x4 s[2][RB];
+          tile_qk<RB>(ktile, qf, s, lane);
+          const bool edge = tb + kTileTokens > cur.L - n_q;
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) s[sub][rb] *= c2 * ks[sub];
+            if (edge) {
+              const int r = 16 * rb + n;
+              const int last = cur.L - n_q + (r < R ? r / G : n_q - 1);
+#pragma unroll
+              for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                  if (tb + 16 * sub + 4 * g4 + i > last) s[sub][rb][i] = -INFINITY;
+            }
+            const float mx = fmaxf(fmaxf(fmaxf(s[0][rb][0], s[0][rb][1]), fmaxf(s[0][rb][2], s[0][rb][3])),
+                                   fmaxf(fmaxf(s[1][rb][0], s[1][rb][1]), fmaxf(s[1][rb][2], s[1][rb][3])));
+            const float m_new = fmaxf(m_run[rb], mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sum += fast_exp2(s[0][rb][i] - m_use) + fast_exp2(s[1][rb][i] - m_use);
+            l_run[rb] = l_run[rb] * fast_exp2(m_run[rb] - m_use) + sum;
+            m_run[rb] = m_new;
+          }
+          PILLAR_TRACE(12);
+        }
+      } else {
+        issue_fetch<FP8>(kv, fetch_of(kv, pnd, pnd_pg, wave, true, wave < nt_pnd), geo, rk, rv);
+      }
+      kv_ahead = has_pnd;
+      PILLAR_TRACE(2);
+      // the 4 token groups of a row, then (through LDS) the 4 wavefronts
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        float mx = fmaxf(m_run[rb], xor16(m_run[rb]));
+        mx = fmaxf(mx, xor32(mx));
+        const float m_use = (mx == -INFINITY) ? 0.f : mx;
+        float l = l_run[rb] * fast_exp2(m_run[rb] - m_use);
+        l += xor16(l);
+        l += xor32(l);
+        if (g4 == 0) { s_m[wave][16 * rb + n] = mx; s_l[wave][16 * rb + n] = l; }
+      }
+      __syncthreads();
+      PILLAR_TRACE(3);
+      // the next slice: its descriptor travels while this one is published
+      const int t_next = s_ticket[parity];
+      if (t_next < total) {
+        has_nxt = true;
+        nxt = decode_slice(kv, ws, t_next);
+        nxt_pg = load_pages(kv, nxt, lane);
+      }
+      if (wave == 0) {
+        if (lane < RB * 16) {
+          float m = -INFINITY;
+#pragma unroll
+          for (int w = 0; w < kWaves; ++w) m = fmaxf(m, s_m[w][lane]);
+          const float m_use = (m == -INFINITY) ? 0.f : m;
+          float l = 0.f;
+#pragma unroll
+          for (int w = 0; w < kWaves; ++w) l += s_l[w][lane] * fast_exp2(s_m[w][lane] - m_use);
+          publish(&ws.part_m[static_cast<int64_t>(cur.id) * (RB * 16) + lane], m);
+          publish(&ws.part_l[static_cast<int64_t>(cur.id) * (RB * 16) + lane], l);
+        }
+        wait_stores();
+        int old = 0;
+        if (lane == 0) old = atomicAdd(&ws.cnt1[cur.pair], 1);
+        old = __builtin_amdgcn_readfirstlane(old);
+        if (old == cur.nslices - 1) {             // every slice of the pair has published: final log-sum-exp
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+          if (lane < RB * 16) {
+            const float* pm = ws.part_m + static_cast<int64_t>(cur.first) * (RB * 16) + lane;
+            const float* pl = ws.part_l + static_cast<int64_t>(cur.first) * (RB * 16) + lane;
+            float m = -INFINITY;
+#pragma unroll 8
+            for (int c = 0; c < cur.nslices; ++c) m = fmaxf(m, pm[c * (RB * 16)]);
+            float l = 0.f;
+#pragma unroll 8
+            for (int c = 0; c < cur.nslices; ++c) l += pl[c * (RB * 16)] * fast_exp2(pm[c * (RB * 16)] - m);
+            // rows beyond R get +inf so that their probabilities vanish in phase 2
+            const float v = lane < R ? m + log2f(l) : INFINITY;
+            publish(&ws.lse2[static_cast<int64_t>(cur.pair) * (RB * 16) + lane], v);
+            if (lse_out && lane < R) {
+              const int i = lane / G, hg = lane - i * G;
+              lse_out[(static_cast<int64_t>(cur.b) * n_q + i) * kv.num_q_heads + cur.g * G + hg] = v * kLn2;
+            }
+          }
+          wait_stores();
+          if (lane == 0) __hip_atomic_store(&ws.ready[cur.pair], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    }
+
+    PILLAR_TRACE(4);
+    // ============ phase 2 of the previous slice: scores, O (K again, V) ============
+    if (has_pnd) {
+      if (threadIdx.x == 0) {
+        int spins = 0;
+        while (!(ws.debug & 4) && __hip_atomic_load(&ws.ready[pnd.pair], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0 && spins < kSpinLimit) {
+          __builtin_amdgcn_s_sleep(16);
+          ++spins;
+        }
+        s_flag = spins < kSpinLimit ? 1 : 0;
+        if (spins >= kSpinLimit) atomicAdd(&ws.ctrl[2], 1);
+      }
+      __syncthreads();                           // also: s_q is complete
+      PILLAR_TRACE(5);
+      const bool ok = s_flag != 0;
+      // what this wave fetches once it has issued its last tile of this phase
+      const Fetch after = has_nxt ? fetch_of(kv, nxt, nxt_pg, wave, false, wave < tiles_of(nxt))
+                                  : fetch_of(kv, cur, cur_pg, wave, true, has_cur && wave < tiles_of(cur));
+      if (ok) {
+        const int nt = nt_pnd;
+        f32x4 o[RB][8];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int d = 0; d < 8; ++d) o[rb][d] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (wave < nt) {
+          const int pg = pnd_pg;
+          if (!kv_ahead) issue_fetch<FP8>(kv, fetch_of(kv, pnd, pg, wave, true, true), geo, rk, rv);
+          float lse2[RB];
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb) lse2[rb] = peek(&ws.lse2[static_cast<int64_t>(pnd.pair) * (RB * 16) + 16 * rb + n]);
+          float* sdst = scores + (static_cast<int64_t>(pnd.b) * kv.num_kv_heads + pnd.g) * score_stride;
+          for (int ti = wave; ti < nt; ti += kWaves) {
+            const int tb = pnd.t_begin + ti * kTileTokens;
+            PILLAR_TRACE(20);
+            if (tb + kTileTokens > pnd.L) zero_tail_rows<FP8>(rv, tb, pnd.L, geo);
+            rows_to_lds<FP8, false>(rk, ktile, lane);
+            rows_to_lds<FP8, true>(rv, vtile, lane);
+            PILLAR_TRACE(21);
+            float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
+            if constexpr (FP8) { half_scales(kv, pnd, tb, pg, kv.k_scale, ks); half_scales(kv, pnd, tb, pg, kv.v_scale, vs); }
+            issue_fetch<FP8>(kv, pick(ti + kWaves < nt, fetch_of(kv, pnd, pg, ti + kWaves, true, true), after), geo, rk, rv);
+            f32x4 s[2][RB];
+            tile_qk_ldsq<RB>(ktile, s_q, R, s, lane);
+            const bool edge = tb + kTileTokens > pnd.L - n_q;
+            f32x4 tot[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+            bf16x8 p[RB];
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+              f32x4 pr[2];
+#pragma unroll
+              for (int sub = 0; sub < 2; ++sub) {
+                const float sc = c2 * ks[sub];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pr[sub][i] = fast_exp2(fmaf(s[sub][rb][i], sc, -lse2[rb]));
+              }
+              if (edge) {
+                const int r = 16 * rb + n;
+                const int last = pnd.L - n_q + (r < R ? r / G : n_q - 1);
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                  for (int i = 0; i < 4; ++i)
+                    if (tb + 16 * sub + 4 * g4 + i > last) pr[sub][i] = 0.f;
+              }
+              tot[0] += pr[0];
+              tot[1] += pr[1];
+              if constexpr (FP8) { pr[0] *= vs[0]; pr[1] *= vs[1]; }
+              p[rb] = pack_p(pr[0], pr[1]);
+            }
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+              for (int i = 0; i < 4; ++i) tot[sub][i] = row16_sum(tot[sub][i]) * inv_r;
+              const int tok0 = tb + 16 * sub + 4 * g4;
+              if (n == 0) {
+                if (tok0 + 3 < pnd.L) {
+                  *reinterpret_cast<f32x4*>(sdst + tok0) = tot[sub];
+                } else {
+#pragma unroll
+                  for (int i = 0; i < 4; ++i)
+                    if (tok0 + i < pnd.L) sdst[tok0 + i] = tot[sub][i];
+                }
+              }
+            }
+            tile_pv<RB>(vtile, p, o, lane);
+            PILLAR_TRACE(22);
+          }
+        } else {
+          issue_fetch<FP8>(kv, after, geo, rk, rv);
+        }
+        PILLAR_TRACE(6);
+        // O of the slice = sum over the four wavefronts: waves 1..3 park theirs in LDS, wave 0 adds
+        f32x4* xch = reinterpret_cast<f32x4*>(smem);
+        constexpr int kHalves = RB > 2 ? 2 : 1;
+        constexpr int kDb = 8 / kHalves;
+        __syncthreads();                     // every wave is done reading its tiles
+#pragma unroll
+        for (int h = 0; h < kHalves; ++h) {
+          if (wave > 0) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+              for (int d = 0; d < kDb; ++d) xch[((wave - 1) * RB * kDb + rb * kDb + d) * 64 + lane] = o[rb][h * kDb + d];
+          }
+          __syncthreads();
+          if (wave == 0) {
+#pragma unroll
+            for (int w = 0; w < kWaves - 1; ++w)
+#pragma unroll
+              for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int d = 0; d < kDb; ++d) o[rb][h * kDb + d] += xch[(w * RB * kDb + rb * kDb + d) * 64 + lane];
+          }
+          __syncthreads();                   // LDS free again (next half / next phase's tiles)
+        }
+        PILLAR_TRACE(7);
+        if (wave == 0) {
+          if (pnd.nslices == 1) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+              const int r = 16 * rb + n;
+              if (r < R) {
+                const int i = r / G, hg = r - i * G;
+                uint16_t* dst = out + ((static_cast<int64_t>(pnd.b) * n_q + i) * kv.num_q_heads + pnd.g * G + hg) * kHeadDim;
+#pragma unroll
+                for (int db = 0; db < 8; ++db) {
+                  u32x2 pk;
+                  pk.x = pack2(o[rb][db][0], o[rb][db][1]);
+                  pk.y = pack2(o[rb][db][2], o[rb][db][3]);
+                  *reinterpret_cast<u32x2*>(dst + 16 * db + 4 * g4) = pk;
+                }
+              }
+            }
+          } else {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+              const int r = 16 * rb + n;
+              if (r < R) {
+                float* dst = ws.part_o + (static_cast<int64_t>(pnd.id) * R + r) * kHeadDim;
+                if (!(ws.debug & 2)) publish_row(dst + 4 * g4, o[rb]);
+              }
+            }
+            wait_stores();
+            int old = 0;
+            if (lane == 0) old = atomicAdd(&ws.cnt2[pnd.pair], 1);
+            old = __builtin_amdgcn_readfirstlane(old);
+            if (old == pnd.nslices - 1) {        // last slice of the pair: O = sum of the slice partials
+              __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+              for (int idx = lane; idx < R * (kHeadDim / 4); idx += 64) {
+                const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+                for (int c = 0; c < pnd.nslices; ++c)
+                  acc += *reinterpret_cast<const f32x4*>(ws.part_o + (static_cast<int64_t>(pnd.first + c) * R + r) * kHeadDim + 4 * d4);
+                const int i = r / G, hg = r - i * G;
+                uint16_t* dst = out + ((static_cast<int64_t>(pnd.b) * n_q + i) * kv.num_q_heads + pnd.g * G + hg) * kHeadDim;
+                u32x2 pk;
+                pk.x = pack2(acc.x, acc.y);
+                pk.y = pack2(acc.z, acc.w);
+                *reinterpret_cast<u32x2*>(dst + 4 * d4) = pk;
+              }
+            }
+          }
+        }
+      } else {
+        // the pair never became ready: make the failure visible instead of hanging
+        float* sdst = scores + (static_cast<int64_t>(pnd.b) * kv.num_kv_heads + pnd.g) * score_stride;
+        for (int t = pnd.t_begin + threadIdx.x; t < pnd.t_end; t += kThreads) sdst[t] = __uint_as_float(0x7fc00000u);
+        issue_fetch<FP8>(kv, after, geo, rk, rv);
+        __syncthreads();
+      }
+      k_ahead = has_nxt;
+      kv_ahead = !has_nxt && has_cur;
+    } else {
+      k_ahead = false;
+    }
+    PILLAR_TRACE(8);
+    pnd = cur;
+    pnd_pg = cur_pg;
+    has_pnd = has_cur;
+  }
+  if ((ws.debug & 16) && blockIdx.x == 0 && threadIdx.x == 0) ws.trace[0] = tr_n;
+}
+
+FusedWs carve(const KvView& kv, int n_q, int slice_tokens, void* workspace, size_t* total_bytes) {
+  const int G = kv.num_q_heads / kv.num_kv_heads;
+  const size_t R = static_cast<size_t>(n_q) * G;
+  const size_t rpad = (R + 15) / 16 * 16;
+  const size_t pairs = static_cast<size_t>(kv.batch) * kv.num_kv_heads;
+  const size_t max_slices = pairs * slices_of(kv.max_seq_len, slice_tokens);
+  char* p = static_cast<char*>(workspace);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { char* r = p ? p + off : nullptr; off += align_up(bytes, 256); return r; };
+  FusedWs w;
+  w.ctrl = reinterpret_cast<int32_t*>(take(64 * 4));
+  w.slice_base = reinterpret_cast<int32_t*>(take((static_cast<size_t>(kv.batch) + 1) * 4));
+  w.slices = reinterpret_cast<int32_t*>(take(max_slices * 16));
+  w.cnt1 = reinterpret_cast<int32_t*>(take(pairs * 4));
+  w.cnt2 = reinterpret_cast<int32_t*>(take(pairs * 4));
+  w.ready = reinterpret_cast<int32_t*>(take(pairs * 4));
+  w.part_m = reinterpret_cast<float*>(take(max_slices * rpad * 4));
+  w.part_l = reinterpret_cast<float*>(take(max_slices * rpad * 4));
+  w.part_o = reinterpret_cast<float*>(take(max_slices * R * kHeadDim * 4));
+  w.lse2 = reinterpret_cast<float*>(take(pairs * rpad * 4));
+  w.trace = reinterpret_cast<long long*>(take(8192 * 8));
+  w.slice_tokens = slice_tokens;
+  w.debug = options().debug;
+  w.max_slices = static_cast<int32_t>(max_slices);
+  if (total_bytes) *total_bytes = off;
+  return w;
+}
+
+int num_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    cus = v;
+  }
+  return cus;
+}
+
+int pick_slice_tokens(const KvView& kv) {
+  int s = options().verify_chunk > 0 ? options().verify_chunk : kDefaultSlice;
+  const int cap = 64 * kv.page_size;              // page ids of a slice live in one register per lane
+  if (s > cap) s = cap;
+  return s;
+}
+
+int grid_size() { return (options().verify_grid > 0 ? options().verify_grid : 2) * num_cus(); }
+
+template <int RB, bool FP8>
+hipError_t run(const VerifyArgs& a, hipStream_t st) {
+  const KvView& kv = a.kv;
+  const FusedWs ws = carve(kv, a.n_q, pick_slice_tokens(kv), a.workspace, nullptr);
+  static bool attr_done = false;
+  if (!attr_done) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_fused_mfma<RB, FP8>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  {
+    KernelTimer t("verify_fused_plan", st);
+    hipLaunchKernelGGL(fused_plan, dim3(1), dim3(1024), 0, st, kv, ws);
+  }
+  {
+    KernelTimer t("verify_fused_mfma", st);
+    hipLaunchKernelGGL((verify_fused_mfma<RB, FP8>), dim3(grid_size()), dim3(kThreads), kLdsBytes, st, kv,
+                       static_cast<const uint16_t*>(a.q), a.n_q, ws, static_cast<uint16_t*>(a.out), a.lse, a.scores,
+                       a.score_stride);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool verify_fused_supported(const VerifyArgs& a) {
+  if (!a.scores || !verify_mfma_supported(a)) return false;
+  const KvView& kv = a.kv;
+  if (kv.batch > kMaxBatchInLds) return false;
+  // every workgroup can park two slices: a pair must fit in what the resident grid can hold
+  if (slices_of(kv.max_seq_len, pick_slice_tokens(kv)) > grid_size()) return false;
+  return true;
+}
+
+size_t verify_fused_trace_offset(const KvView& kv, int n_q) {
+  const FusedWs w = carve(kv, n_q, pick_slice_tokens(kv), reinterpret_cast<void*>(0x1000), nullptr);
+  return reinterpret_cast<uintptr_t>(w.trace) - 0x1000;
+}
+
+size_t verify_fused_workspace(const KvView& kv, int n_q) {
+  size_t total = 0;
+  carve(kv, n_q, pick_slice_tokens(kv), nullptr, &total);
+  return total;
+}
+
+hipError_t launch_verify_fused(const VerifyArgs& a, hipStream_t s) {
+  const int G = a.kv.num_q_heads / a.kv.num_kv_heads;
+  const int rb = (a.n_q * G + 15) / 16;
+  const bool fp8 = a.kv_dtype == PILLAR_FP8_E4M3;
+#define PILLAR_CASE(N) \
+  if (rb == N) return fp8 ? run<N, true>(a, s) : run<N, false>(a, s);
+  PILLAR_CASE(1)
+  PILLAR_CASE(2)
+  PILLAR_CASE(3)
+  PILLAR_CASE(4)
+#undef PILLAR_CASE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace pillar

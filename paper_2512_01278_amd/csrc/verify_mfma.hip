@@ -27,7 +27,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kChunk = 512;                 // tokens per work item
-constexpr int kLdsBytes = kWaves * kWaveLds;  // 64 KiB
+constexpr int kLdsBytes = kWaves * kWaveLds;
 
 struct FastWs {
   int32_t* ctrl;        // [0] split ticket, [1] scores ticket, [2] item count
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_split_mfma(KvView kv, cons
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 15, g4 = lane >> 4;
   uint8_t* ktile = smem + wave * kWaveLds;
-  uint8_t* vtile = ktile + kTileBytes;
+  uint8_t* vtile = ktile + kKTileBytes;
   const int G = kv.num_q_heads / kv.num_kv_heads;
   const int R = n_q * G;
   const float c2 = kv.sm_scale * kLog2e;
@@ -373,7 +373,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_scores_mfma(KvView kv, con
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 15, g4 = lane >> 4;
   uint8_t* ktile = smem + wave * kWaveLds;
-  uint8_t* vtile = ktile + kTileBytes;
+  uint8_t* vtile = ktile + kKTileBytes;
   const int G = kv.num_q_heads / kv.num_kv_heads;
   const int R = n_q * G;
   const float c2 = kv.sm_scale * kLog2e;
