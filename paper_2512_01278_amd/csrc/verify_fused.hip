@@ -13,38 +13,40 @@
 // 2 GB while re-reading data touched 64 MB earlier costs about 10 % more time
 // than streaming alone).  A logit dump would add 16..60 % HBM traffic.
 //
-// Each (request, KV head) is cut into slices of `slice_tokens` tokens.  A
-// slice is visited twice by the same workgroup:
+// Each (request, KV head) is cut into slices of `slice_tokens` tokens, and a
+// slice is the work of ONE wavefront (a workgroup is one wavefront: nothing in
+// this kernel needs a barrier).  The wavefront visits its slice twice:
 //   phase 1  K only: S^T = K Q^T on the matrix cores, running (max, sum) per
-//            row -> the slice's (m, l).  The last slice of a pair to finish
-//            combines all (m, l) of the pair into the final log-sum-exp.
-//   phase 2  K (from the Infinity Cache) and V: p = exp2(s - lse) is the exact
-//            probability, so the score statistic is written directly, and
-//            O = sum p V needs no running maximum and no rescaling; slice
+//            row -> the slice's (m, l), published.  The last slice of a pair
+//            to publish combines all (m, l) into the final log-sum-exp.
+//   wait     until the pair's log-sum-exp is there.  The slices of a pair are
+//            handed out together, so this takes a few microseconds, during
+//            which the other wavefronts of the compute unit keep HBM busy.
+//   phase 2  K (now from the Infinity Cache) and V: p = exp2(s - lse) is the
+//            exact probability, so the score statistic is written directly,
+//            and O = sum p V needs no running maximum and no rescaling; slice
 //            partials of O add linearly and the last slice to finish sums them.
-// A workgroup interleaves the two: phase 1 of its next slice, then phase 2 of
-// the previous one, so that the pair of the previous slice has normally been
-// completed by the other workgroups in the meantime and nobody waits.
 //
-// Progress: slices are handed out by one atomic ticket in pair-major order; a
-// workgroup waits (phase 2) only for slices whose tickets were handed out, and
-// a workgroup holding a ticket never waits before its phase 1 is published.
-// Every workgroup can hold two slices, so a pair completes as long as it has at
-// most 2 x (resident workgroups) slices; the host only selects this kernel
-// below that bound, and the wait is a bounded spin that counts a timeout in
-// the workspace instead of hanging.
+// Progress: slices are handed out by one atomic ticket in pair-major order.  A
+// wavefront holds one slice; it publishes phase 1 before it waits, and waits
+// only for slices of its own pair.  The lowest slice nobody has taken yet
+// belongs to some pair; every wavefront waiting on another pair is released
+// once that pair's (already taken, never waiting) phase-1 work is done, and
+// the pair itself cannot occupy every wavefront as long as it has no more
+// slices than there are resident wavefronts: the host selects this kernel only
+// below that bound.  The wait is a bounded spin that poisons the slice's
+// scores with NaN instead of hanging.
 #include "launch.hpp"
 #include "mfma_tile.hpp"
 
 namespace pillar {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
-constexpr int kLdsBytes = kWaves * kWaveLds;
+constexpr int kThreads = 64;                   // one wavefront per workgroup
 constexpr int kSpinLimit = 1 << 20;
 constexpr int kDefaultSlice = 512;
 constexpr int kMaxBatchInLds = 4096;
+constexpr int kWavesPerCu = 8;
 
 struct FusedWs {
   int32_t* ctrl;        // [0] ticket  [1] slice count  [2] timeouts
@@ -60,7 +62,7 @@ struct FusedWs {
   int32_t slice_tokens;
   int32_t max_slices;
   int32_t debug;
-  long long* trace;     // [8192] timestamps of workgroup 0 when debug bit 16 is set
+  long long* trace;     // [8192] timestamps of workgroup 0 (tracing builds only)
 };
 
 __host__ __device__ inline int slices_of(int len, int slice_tokens) { return (len + slice_tokens - 1) / slice_tokens; }
@@ -137,7 +139,7 @@ __device__ __forceinline__ Slice decode_slice(const KvView& kv, const FusedWs& w
   s.t_begin = s.c * ws.slice_tokens;
   s.t_end = min(s.L, s.t_begin + ws.slice_tokens);
   s.nslices = slices_of(s.L, ws.slice_tokens);
-  s.first = id - s.c;                       // slice 0 of this (request, head)
+  s.first = s.id - s.c;                     // slice 0 of this (request, head)
   s.pair = s.b * kv.num_kv_heads + s.g;
   return s;
 }
@@ -160,6 +162,7 @@ __device__ __forceinline__ void load_q(const KvView& kv, const uint16_t* q, int 
   }
 }
 
+// lane j: page id of page (first page of the slice + j) of the request
 __device__ __forceinline__ int load_pages(const KvView& kv, const Slice& it, int lane) {
   const int first_page = it.t_begin >> kv.page_shift;
   const int last_page = (it.L - 1) >> kv.page_shift;
@@ -191,7 +194,7 @@ __device__ __forceinline__ LaneGeom<FP8> lane_geom(const KvView& kv, int lane) {
 // pages are whole, so the rows exist; the caller masks them.
 template <bool FP8, bool WITH_V>
 __device__ __forceinline__ void issue_rows(const KvView& kv, const Slice& it, int tb, int pg, const LaneGeom<FP8>& geo,
-                                           u32x4 (&rk)[TileRegs<FP8>::kLoads], u32x4 (&rv)[TileRegs<FP8>::kLoads], int lane) {
+                                           u32x4 (&rk)[TileRegs<FP8>::kLoads], u32x4 (&rv)[TileRegs<FP8>::kLoads]) {
   constexpr int kLoads = TileRegs<FP8>::kLoads;
   constexpr int kPerGroup = kLoads / 2;
   const int esz = FP8 ? 1 : 2;
@@ -208,63 +211,8 @@ __device__ __forceinline__ void issue_rows(const KvView& kv, const Slice& it, in
 #pragma unroll
     for (int u = 0; u < kPerGroup; ++u) {
       const uint32_t off = geo.lane_off + u * geo.row_step;
-      rk[grp * kPerGroup + u] = *reinterpret_cast<const u32x4*>(gk + off);
-      if constexpr (WITH_V) rv[grp * kPerGroup + u] = *reinterpret_cast<const u32x4*>(gv + off);
-    }
-  }
-}
-
-// One tile fetch described by scalars, so that a loop needs a single load site
-// whatever slice and phase the next tile belongs to.
-struct Fetch {
-  int g, first_page, last_page, tb, pg;
-  bool with_v, valid;
-};
-
-__device__ __forceinline__ Fetch fetch_of(const KvView& kv, const Slice& s, int pg, int tile, bool with_v, bool valid) {
-  Fetch f;
-  f.g = s.g;
-  f.first_page = s.t_begin >> kv.page_shift;
-  f.last_page = (s.L - 1) >> kv.page_shift;
-  f.tb = s.t_begin + tile * kTileTokens;
-  f.pg = pg;
-  f.with_v = with_v;
-  f.valid = valid;
-  return f;
-}
-
-__device__ __forceinline__ Fetch pick(bool c, const Fetch& a, const Fetch& b) {
-  Fetch f;
-  f.g = c ? a.g : b.g;
-  f.first_page = c ? a.first_page : b.first_page;
-  f.last_page = c ? a.last_page : b.last_page;
-  f.tb = c ? a.tb : b.tb;
-  f.pg = c ? a.pg : b.pg;
-  f.with_v = c ? a.with_v : b.with_v;
-  f.valid = c ? a.valid : b.valid;
-  return f;
-}
-
-template <bool FP8>
-__device__ __forceinline__ void issue_fetch(const KvView& kv, const Fetch& f, const LaneGeom<FP8>& geo,
-                                            u32x4 (&rk)[TileRegs<FP8>::kLoads], u32x4 (&rv)[TileRegs<FP8>::kLoads]) {
-  if (!f.valid) return;
-  constexpr int kLoads = TileRegs<FP8>::kLoads;
-  constexpr int kPerGroup = kLoads / 2;
-  const int esz = FP8 ? 1 : 2;
-#pragma unroll
-  for (int grp = 0; grp < 2; ++grp) {
-    const int tok0 = f.tb + 16 * grp;
-    const int page = __builtin_amdgcn_readlane(f.pg, min(tok0 >> kv.page_shift, f.last_page) - f.first_page);
-    const int64_t base = (static_cast<int64_t>(page) * kv.stride_page + static_cast<int64_t>(f.g) * kv.stride_head +
-                          static_cast<int64_t>(tok0 & (kv.page_size - 1)) * kv.stride_slot) * esz;
-    const char* gk = static_cast<const char*>(kv.k_pool) + base;
-    const char* gv = static_cast<const char*>(kv.v_pool) + base;
-#pragma unroll
-    for (int u = 0; u < kPerGroup; ++u) rk[grp * kPerGroup + u] = *reinterpret_cast<const u32x4*>(gk + (geo.lane_off + u * geo.row_step));
-    if (f.with_v) {
-#pragma unroll
-      for (int u = 0; u < kPerGroup; ++u) rv[grp * kPerGroup + u] = *reinterpret_cast<const u32x4*>(gv + (geo.lane_off + u * geo.row_step));
+      rk[grp * kPerGroup + u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gk + off));
+      if constexpr (WITH_V) rv[grp * kPerGroup + u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gv + off));
     }
   }
 }
@@ -300,14 +248,14 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
-// ---------------------------------------------------------------- kernel ----
-// stores that other workgroups (possibly on another XCD, behind another L2)
-// will read: written through to memory, so that publishing them needs no L2
-// write-back, only a wait for the acknowledgements
+// Stores that another wavefront (possibly on another XCD, behind another L2)
+// will read are written through to memory (sc1), so publishing them needs no
+// L2 write-back, only a wait for the acknowledgements; the reader either loads
+// with sc1 or invalidates once (acquire fence) before plain loads.
 __device__ __forceinline__ void publish(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void publish4(float* p, const f32x4& v) {
-  publish(p, v.x); publish(p + 1, v.y); publish(p + 2, v.z); publish(p + 3, v.w);
-}
+__device__ __forceinline__ float peek(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void wait_stores() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+
 // eight 16-byte write-through stores (dims 16db + 4g .. +3 of one row) and the wait for their acknowledgement
 __device__ __forceinline__ void publish_row(float* p, const f32x4 (&v)[8]) {
   asm volatile(
@@ -324,12 +272,11 @@ __device__ __forceinline__ void publish_row(float* p, const f32x4 (&v)[8]) {
       : "v"(p), "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "v"(v[4]), "v"(v[5]), "v"(v[6]), "v"(v[7])
       : "memory");
 }
-__device__ __forceinline__ float peek(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ void wait_stores() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
 __device__ __forceinline__ int tiles_of(const Slice& s) { return (s.t_end - s.t_begin + kTileTokens - 1) / kTileTokens; }
 
-// S^T of the tile with the Q operand read from LDS (rows in K-tile layout)
+// S^T of the tile with the Q operand read from LDS: rows 0..R-1 in K-tile layout
+// followed by one row of zeros that every padded row of the last block reads.
 template <int RB>
 __device__ __forceinline__ void tile_qk_ldsq(const uint8_t* ktile, const uint8_t* qtile, int R, f32x4 (&acc)[2][RB], int lane) {
   const int n = lane & 15, g = lane >> 4;
@@ -355,26 +302,21 @@ __device__ __forceinline__ void tile_qk_ldsq(const uint8_t* ktile, const uint8_t
 }
 
 #ifdef PILLAR_TRACING
-#define PILLAR_TRACE(tag) do { if ((ws.debug & 16) && blockIdx.x == 0 && threadIdx.x == 0 && tr_n < 8190) { ws.trace[tr_n++] = (static_cast<long long>(tag) << 48) | (wall_clock64() & 0xffffffffffffll); } } while (0)
+#define PILLAR_TRACE(tag) do { if (blockIdx.x == 0 && threadIdx.x == 0 && tr_n < 8190) { ws.trace[tr_n++] = (static_cast<long long>(tag) << 48) | (wall_clock64() & 0xffffffffffffll); } } while (0)
 #else
 #define PILLAR_TRACE(tag) do { } while (0)
 #endif
 
+// ---------------------------------------------------------------- kernel ----
 template <int RB, bool FP8>
 __global__ __launch_bounds__(kThreads, 2) void verify_fused_mfma(KvView kv, const uint16_t* q, int n_q, FusedWs ws,
                                                                  uint16_t* out, float* lse_out, float* scores,
                                                                  int64_t score_stride) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-  __shared__ int s_ticket[2], s_flag;
-  __shared__ float s_m[kWaves][RB * 16], s_l[kWaves][RB * 16];
-  // Q rows of the phase-2 slice in K-tile layout: rows 0..R-1, then one row of zeros that
-  // stands in for every padded row of the last 16-row block
+  // one tile buffer: K rows in phase 1; in phase 2 K rows, then (once S^T is done) the V rows of the same tile
+  __shared__ __attribute__((aligned(16))) uint8_t s_tile[kVTileBytes];
   __shared__ __attribute__((aligned(16))) uint8_t s_q[(RB * 16 + 1) * kKRow];
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x;
   const int n = lane & 15, g4 = lane >> 4;
-  uint8_t* ktile = smem + wave * kWaveLds;
-  uint8_t* vtile = ktile + kKTileBytes;
   const int G = kv.num_q_heads / kv.num_kv_heads;
   const int R = n_q * G;
   const float c2 = kv.sm_scale * kLog2e;
@@ -382,103 +324,105 @@ __global__ __launch_bounds__(kThreads, 2) void verify_fused_mfma(KvView kv, cons
   const int total = ws.ctrl[1];
   const LaneGeom<FP8> geo = lane_geom<FP8>(kv, lane);
   constexpr int kLoads = TileRegs<FP8>::kLoads;
-
-  // registers of the tile in flight: the last tile of a phase already fetches
-  // the first tile of the next phase, so they live across phases
-  u32x4 rk[kLoads], rv[kLoads];
-  Slice nxt = {}, pnd = {};
-  int nxt_pg = 0, pnd_pg = 0;
-  bool has_nxt = false, has_pnd = false;
-  bool k_ahead = false;            // rk holds this wave's first K tile of `nxt`
-  bool kv_ahead = false;           // rk, rv hold this wave's first tile of `pnd`
-  int parity = 0;
   [[maybe_unused]] int tr_n = 1;
 
-  if (threadIdx.x == 0) s_ticket[0] = atomicAdd(&ws.ctrl[0], 1);
-  __syncthreads();
-  if (s_ticket[0] < total) {
-    has_nxt = true;
-    nxt = decode_slice(kv, ws, s_ticket[0]);
-    nxt_pg = load_pages(kv, nxt, lane);
-  }
+  int ticket = 0;
+  if (lane == 0) ticket = atomicAdd(&ws.ctrl[0], 1);
+  ticket = __builtin_amdgcn_readfirstlane(ticket);
 
-  while (has_nxt || has_pnd) {
-    const Slice cur = nxt;
-    const int cur_pg = nxt_pg;
-    const bool has_cur = has_nxt;
-    const int nt_pnd = has_pnd ? tiles_of(pnd) : 0;
-    parity ^= 1;
-    if (has_cur && threadIdx.x == 0) s_ticket[parity] = atomicAdd(&ws.ctrl[0], 1);   // read after the next barrier
-    has_nxt = false;
-
+  // Software pipeline over the slices of this wavefront: phase 1 of the slice just taken runs
+  // between phase 1 and phase 2 of the previous one, so that the publish / combine / ready
+  // round trips of a pair are hidden behind streaming instead of being waited for.
+  Slice prev = {};
+  int prev_pg = 0;
+  bool has_prev = false;
+  u32x4 rk[kLoads], rv[kLoads];
+  while (ticket < total || has_prev) {
     PILLAR_TRACE(1);
-    // Q rows of the slice whose phase 2 follows: global -> LDS while phase 1 runs
-    if (has_pnd) {
-      for (int ch = threadIdx.x; ch < (R + 1) * 16; ch += kThreads) {
-        const int r = ch >> 4, c = ch & 15;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (r < R) {
-          const int i = r / G, hg = r - i * G;
-          v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(pnd.b) * n_q + i) * kv.num_q_heads + pnd.g * G + hg) * kHeadDim + 8 * c);
-        }
-        *reinterpret_cast<u32x4*>(s_q + k_lds_addr(r, c)) = v;
+    const bool has_cur = ticket < total;
+    Slice cur = {};
+    int cur_pg = 0;
+    if (has_cur) {
+      cur = decode_slice(kv, ws, ticket);
+      cur_pg = load_pages(kv, cur, lane);
+    }
+
+    // Q rows of the previous slice's pair -> LDS for its phase 2
+    if (has_prev) {
+    const Slice& it = prev;
+    for (int ch = lane; ch < (R + 1) * 16; ch += kThreads) {
+      const int r = ch >> 4, c = ch & 15;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (r < R) {
+        const int i = r / G, hg = r - i * G;
+        v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(it.b) * n_q + i) * kv.num_q_heads + it.g * G + hg) * kHeadDim + 8 * c);
       }
+      *reinterpret_cast<u32x4*>(s_q + k_lds_addr(r, c)) = v;
+    }
     }
 
     // =================== phase 1: K only -> (m, l) of the slice ===================
     if (has_cur) {
-      const int nt = tiles_of(cur);
+      const Slice& it = cur;
+      const int pg = cur_pg;
+      const int nt = tiles_of(it);
+      bf16x8 qf[RB][4];
+      load_q<RB>(kv, q, n_q, G, R, it, qf, lane);
       float m_run[RB], l_run[RB];
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) { m_run[rb] = -INFINITY; l_run[rb] = 0.f; }
-      if (wave < nt) {
-        bf16x8 qf[RB][4];
-        load_q<RB>(kv, q, n_q, G, R, cur, qf, lane);
-        const int pg = cur_pg;
-        if (!k_ahead) issue_fetch<FP8>(kv, fetch_of(kv, cur, pg, wave, false, true), geo, rk, rv);
-        const Fetch after = fetch_of(kv, pnd, pnd_pg, wave, true, wave < nt_pnd);   // first tile of phase 2
-        for (int ti = wave; ti < nt; ti += kWaves) {
-          const int tb = cur.t_begin + ti * kTileTokens;
-          PILLAR_TRACE(10);
-          rows_to_lds<FP8, false>(rk, ktile, lane);
-          PILLAR_TRACE(11);
-          float ks[2] = {1.f, 1.f};
-          if constexpr (FP8) half_scales(kv, cur, tb, pg, kv.k_scale, ks);
-          issue_fetch<FP8>(kv, pick(ti + kWaves < nt, fetch_of(kv, cur, pg, ti + kWaves, false, true), after), geo, rk, rv);
-          f32x4 s[2][RB];
-          tile_qk<RB>(ktile, qf, s, lane);
-          const bool edge = tb + kTileTokens > cur.L - n_q;
-#pragma unroll
-          for (int rb = 0; rb < RB; ++rb) {
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub) s[sub][rb] *= c2 * ks[sub];
-            if (edge) {
-              const int r = 16 * rb + n;
-              const int last = cur.L - n_q + (r < R ? r / G : n_q - 1);
-#pragma unroll
-              for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                  if (tb + 16 * sub + 4 * g4 + i > last) s[sub][rb][i] = -INFINITY;
-            }
-            const float mx = fmaxf(fmaxf(fmaxf(s[0][rb][0], s[0][rb][1]), fmaxf(s[0][rb][2], s[0][rb][3])),
-                                   fmaxf(fmaxf(s[1][rb][0], s[1][rb][1]), fmaxf(s[1][rb][2], s[1][rb][3])));
-            const float m_new = fmaxf(m_run[rb], mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            float sum = 0.f;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) sum += fast_exp2(s[0][rb][i] - m_use) + fast_exp2(s[1][rb][i] - m_use);
-            l_run[rb] = l_run[rb] * fast_exp2(m_run[rb] - m_use) + sum;
-            m_run[rb] = m_new;
-          }
-          PILLAR_TRACE(12);
-        }
-      } else {
-        issue_fetch<FP8>(kv, fetch_of(kv, pnd, pnd_pg, wave, true, wave < nt_pnd), geo, rk, rv);
-      }
-      kv_ahead = has_pnd;
+      // K tiles travel two deep: even tiles through rk, odd tiles through rv (V is not read in this phase)
+      u32x4 unused[kLoads];
+      issue_rows<FP8, false>(kv, it, it.t_begin, pg, geo, rk, unused);
+      if (nt > 1) issue_rows<FP8, false>(kv, it, it.t_begin + kTileTokens, pg, geo, rv, unused);
       PILLAR_TRACE(2);
-      // the 4 token groups of a row, then (through LDS) the 4 wavefronts
+      auto phase1_tile = [&](int ti, u32x4 (&regs)[kLoads]) {
+        const int tb = it.t_begin + ti * kTileTokens;
+        if (ws.debug & 256) {                      // experiment: memory traffic only
+          u32x4 x = regs[0];
+#pragma unroll
+          for (int u = 1; u < kLoads; ++u) x ^= regs[u];
+          if (ti + 2 < nt) issue_rows<FP8, false>(kv, it, tb + 2 * kTileTokens, pg, geo, regs, unused);
+          l_run[0] += __uint_as_float((x.x ^ x.y ^ x.z ^ x.w) & 0x3fffffffu);
+          return;
+        }
+        rows_to_lds<FP8, false>(regs, s_tile, lane);
+        float ks[2] = {1.f, 1.f};
+        if constexpr (FP8) half_scales(kv, it, tb, pg, kv.k_scale, ks);
+        if (ti + 2 < nt) issue_rows<FP8, false>(kv, it, tb + 2 * kTileTokens, pg, geo, regs, unused);
+        f32x4 s[2][RB];
+        tile_qk<RB>(s_tile, qf, s, lane);
+        const bool edge = tb + kTileTokens > it.L - n_q;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+          for (int sub = 0; sub < 2; ++sub) s[sub][rb] *= c2 * ks[sub];
+          if (edge) {
+            const int r = 16 * rb + n;
+            const int last = it.L - n_q + (r < R ? r / G : n_q - 1);
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+              for (int i = 0; i < 4; ++i)
+                if (tb + 16 * sub + 4 * g4 + i > last) s[sub][rb][i] = -INFINITY;
+          }
+          const float mx = fmaxf(fmaxf(fmaxf(s[0][rb][0], s[0][rb][1]), fmaxf(s[0][rb][2], s[0][rb][3])),
+                                 fmaxf(fmaxf(s[1][rb][0], s[1][rb][1]), fmaxf(s[1][rb][2], s[1][rb][3])));
+          const float m_new = fmaxf(m_run[rb], mx);
+          const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+          float sum = 0.f;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) sum += fast_exp2(s[0][rb][i] - m_use) + fast_exp2(s[1][rb][i] - m_use);
+          l_run[rb] = l_run[rb] * fast_exp2(m_run[rb] - m_use) + sum;
+          m_run[rb] = m_new;
+        }
+      };
+      for (int ti = 0; ti < ((ws.debug & 512) ? 0 : nt); ti += 2) {
+        phase1_tile(ti, rk);
+        if (ti + 1 < nt) phase1_tile(ti + 1, rv);
+      }
+      PILLAR_TRACE(3);
+      // the 4 token groups of a row -> the slice's (m, l), published by the lanes of group 0
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         float mx = fmaxf(m_run[rb], xor16(m_run[rb]));
@@ -487,241 +431,208 @@ __global__ __launch_bounds__(kThreads, 2) void verify_fused_mfma(KvView kv, cons
         float l = l_run[rb] * fast_exp2(m_run[rb] - m_use);
         l += xor16(l);
         l += xor32(l);
-        if (g4 == 0) { s_m[wave][16 * rb + n] = mx; s_l[wave][16 * rb + n] = l; }
+        if (g4 == 0) {
+          publish(&ws.part_m[static_cast<int64_t>(it.id) * (RB * 16) + 16 * rb + n], mx);
+          publish(&ws.part_l[static_cast<int64_t>(it.id) * (RB * 16) + 16 * rb + n], l);
+        }
       }
-      __syncthreads();
-      PILLAR_TRACE(3);
-      // the next slice: its descriptor travels while this one is published
-      const int t_next = s_ticket[parity];
-      if (t_next < total) {
-        has_nxt = true;
-        nxt = decode_slice(kv, ws, t_next);
-        nxt_pg = load_pages(kv, nxt, lane);
-      }
-      if (wave == 0) {
+      wait_stores();
+      int old = 0;
+      if (lane == 0) old = atomicAdd(&ws.cnt1[it.pair], 1);
+      // the first tile of the previous slice's phase 2 travels meanwhile
+      if (has_prev) issue_rows<FP8, true>(kv, prev, prev.t_begin, prev_pg, geo, rk, rv);
+      old = __builtin_amdgcn_readfirstlane(old);
+      if (old == it.nslices - 1) {               // every slice of the pair has published: final log-sum-exp
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         if (lane < RB * 16) {
+          const float* pm = ws.part_m + static_cast<int64_t>(it.first) * (RB * 16) + lane;
+          const float* pl = ws.part_l + static_cast<int64_t>(it.first) * (RB * 16) + lane;
           float m = -INFINITY;
-#pragma unroll
-          for (int w = 0; w < kWaves; ++w) m = fmaxf(m, s_m[w][lane]);
-          const float m_use = (m == -INFINITY) ? 0.f : m;
+#pragma unroll 8
+          for (int c = 0; c < it.nslices; ++c) m = fmaxf(m, pm[c * (RB * 16)]);
           float l = 0.f;
-#pragma unroll
-          for (int w = 0; w < kWaves; ++w) l += s_l[w][lane] * fast_exp2(s_m[w][lane] - m_use);
-          publish(&ws.part_m[static_cast<int64_t>(cur.id) * (RB * 16) + lane], m);
-          publish(&ws.part_l[static_cast<int64_t>(cur.id) * (RB * 16) + lane], l);
+#pragma unroll 8
+          for (int c = 0; c < it.nslices; ++c) l += pl[c * (RB * 16)] * fast_exp2(pm[c * (RB * 16)] - m);
+          // rows beyond R get +inf so that their probabilities vanish in phase 2
+          const float v = lane < R ? m + log2f(l) : INFINITY;
+          publish(&ws.lse2[static_cast<int64_t>(it.pair) * (RB * 16) + lane], v);
+          if (lse_out && lane < R) {
+            const int i = lane / G, hg = lane - i * G;
+            lse_out[(static_cast<int64_t>(it.b) * n_q + i) * kv.num_q_heads + it.g * G + hg] = v * kLn2;
+          }
         }
         wait_stores();
-        int old = 0;
-        if (lane == 0) old = atomicAdd(&ws.cnt1[cur.pair], 1);
-        old = __builtin_amdgcn_readfirstlane(old);
-        if (old == cur.nslices - 1) {             // every slice of the pair has published: final log-sum-exp
-          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-          if (lane < RB * 16) {
-            const float* pm = ws.part_m + static_cast<int64_t>(cur.first) * (RB * 16) + lane;
-            const float* pl = ws.part_l + static_cast<int64_t>(cur.first) * (RB * 16) + lane;
-            float m = -INFINITY;
-#pragma unroll 8
-            for (int c = 0; c < cur.nslices; ++c) m = fmaxf(m, pm[c * (RB * 16)]);
-            float l = 0.f;
-#pragma unroll 8
-            for (int c = 0; c < cur.nslices; ++c) l += pl[c * (RB * 16)] * fast_exp2(pm[c * (RB * 16)] - m);
-            // rows beyond R get +inf so that their probabilities vanish in phase 2
-            const float v = lane < R ? m + log2f(l) : INFINITY;
-            publish(&ws.lse2[static_cast<int64_t>(cur.pair) * (RB * 16) + lane], v);
-            if (lse_out && lane < R) {
-              const int i = lane / G, hg = lane - i * G;
-              lse_out[(static_cast<int64_t>(cur.b) * n_q + i) * kv.num_q_heads + cur.g * G + hg] = v * kLn2;
-            }
-          }
-          wait_stores();
-          if (lane == 0) __hip_atomic_store(&ws.ready[cur.pair], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        if (lane == 0) __hip_atomic_store(&ws.ready[it.pair], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
-
+    else if (has_prev) {
+      issue_rows<FP8, true>(kv, prev, prev.t_begin, prev_pg, geo, rk, rv);
+    }
     PILLAR_TRACE(4);
-    // ============ phase 2 of the previous slice: scores, O (K again, V) ============
-    if (has_pnd) {
-      if (threadIdx.x == 0) {
-        int spins = 0;
-        while (!(ws.debug & 4) && __hip_atomic_load(&ws.ready[pnd.pair], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0 && spins < kSpinLimit) {
-          __builtin_amdgcn_s_sleep(16);
-          ++spins;
-        }
-        s_flag = spins < kSpinLimit ? 1 : 0;
-        if (spins >= kSpinLimit) atomicAdd(&ws.ctrl[2], 1);
+
+    // ================= the previous slice: its pair should be complete by now =================
+    if (has_prev) {
+    const Slice& it = prev;
+    const int pg = prev_pg;
+    const int nt = tiles_of(it);
+    bool ok;
+    {
+      int spins = 0;
+      while (__hip_atomic_load(&ws.ready[it.pair], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0 && spins < kSpinLimit) {
+        __builtin_amdgcn_s_sleep(8);
+        ++spins;
       }
-      __syncthreads();                           // also: s_q is complete
-      PILLAR_TRACE(5);
-      const bool ok = s_flag != 0;
-      // what this wave fetches once it has issued its last tile of this phase
-      const Fetch after = has_nxt ? fetch_of(kv, nxt, nxt_pg, wave, false, wave < tiles_of(nxt))
-                                  : fetch_of(kv, cur, cur_pg, wave, true, has_cur && wave < tiles_of(cur));
-      if (ok) {
-        const int nt = nt_pnd;
-        f32x4 o[RB][8];
+      ok = __builtin_amdgcn_readfirstlane(spins) < kSpinLimit;
+    }
+    PILLAR_TRACE(5);
+
+    // ================= phase 2: scores and O (K again, and V) =================
+    float* sdst = scores + (static_cast<int64_t>(it.b) * kv.num_kv_heads + it.g) * score_stride;
+    if (ok) {
+      float lse2[RB];
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
+      for (int rb = 0; rb < RB; ++rb) lse2[rb] = peek(&ws.lse2[static_cast<int64_t>(it.pair) * (RB * 16) + 16 * rb + n]);
+      f32x4 o[RB][8];
 #pragma unroll
-          for (int d = 0; d < 8; ++d) o[rb][d] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (wave < nt) {
-          const int pg = pnd_pg;
-          if (!kv_ahead) issue_fetch<FP8>(kv, fetch_of(kv, pnd, pg, wave, true, true), geo, rk, rv);
-          float lse2[RB];
+      for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-          for (int rb = 0; rb < RB; ++rb) lse2[rb] = peek(&ws.lse2[static_cast<int64_t>(pnd.pair) * (RB * 16) + 16 * rb + n]);
-          float* sdst = scores + (static_cast<int64_t>(pnd.b) * kv.num_kv_heads + pnd.g) * score_stride;
-          for (int ti = wave; ti < nt; ti += kWaves) {
-            const int tb = pnd.t_begin + ti * kTileTokens;
-            PILLAR_TRACE(20);
-            if (tb + kTileTokens > pnd.L) zero_tail_rows<FP8>(rv, tb, pnd.L, geo);
-            rows_to_lds<FP8, false>(rk, ktile, lane);
-            rows_to_lds<FP8, true>(rv, vtile, lane);
-            PILLAR_TRACE(21);
-            float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
-            if constexpr (FP8) { half_scales(kv, pnd, tb, pg, kv.k_scale, ks); half_scales(kv, pnd, tb, pg, kv.v_scale, vs); }
-            issue_fetch<FP8>(kv, pick(ti + kWaves < nt, fetch_of(kv, pnd, pg, ti + kWaves, true, true), after), geo, rk, rv);
-            f32x4 s[2][RB];
-            tile_qk_ldsq<RB>(ktile, s_q, R, s, lane);
-            const bool edge = tb + kTileTokens > pnd.L - n_q;
-            f32x4 tot[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-            bf16x8 p[RB];
+        for (int d = 0; d < 8; ++d) o[rb][d] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int ti = 0; ti < ((ws.debug & 1024) ? 0 : nt); ++ti) {
+        const int tb = it.t_begin + ti * kTileTokens;
+        if (ws.debug & 256) {                      // experiment: memory traffic only
+          u32x4 x = rk[0] ^ rv[0];
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-              f32x4 pr[2];
-#pragma unroll
-              for (int sub = 0; sub < 2; ++sub) {
-                const float sc = c2 * ks[sub];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) pr[sub][i] = fast_exp2(fmaf(s[sub][rb][i], sc, -lse2[rb]));
-              }
-              if (edge) {
-                const int r = 16 * rb + n;
-                const int last = pnd.L - n_q + (r < R ? r / G : n_q - 1);
-#pragma unroll
-                for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                  for (int i = 0; i < 4; ++i)
-                    if (tb + 16 * sub + 4 * g4 + i > last) pr[sub][i] = 0.f;
-              }
-              tot[0] += pr[0];
-              tot[1] += pr[1];
-              if constexpr (FP8) { pr[0] *= vs[0]; pr[1] *= vs[1]; }
-              p[rb] = pack_p(pr[0], pr[1]);
-            }
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-#pragma unroll
-              for (int i = 0; i < 4; ++i) tot[sub][i] = row16_sum(tot[sub][i]) * inv_r;
-              const int tok0 = tb + 16 * sub + 4 * g4;
-              if (n == 0) {
-                if (tok0 + 3 < pnd.L) {
-                  *reinterpret_cast<f32x4*>(sdst + tok0) = tot[sub];
-                } else {
-#pragma unroll
-                  for (int i = 0; i < 4; ++i)
-                    if (tok0 + i < pnd.L) sdst[tok0 + i] = tot[sub][i];
-                }
-              }
-            }
-            tile_pv<RB>(vtile, p, o, lane);
-            PILLAR_TRACE(22);
-          }
-        } else {
-          issue_fetch<FP8>(kv, after, geo, rk, rv);
+          for (int u = 1; u < kLoads; ++u) x ^= rk[u] ^ rv[u];
+          if (ti + 1 < nt) issue_rows<FP8, true>(kv, it, tb + kTileTokens, pg, geo, rk, rv);
+          o[0][0].x += __uint_as_float((x.x ^ x.y ^ x.z ^ x.w) & 0x3fffffffu);
+          continue;
         }
-        PILLAR_TRACE(6);
-        // O of the slice = sum over the four wavefronts: waves 1..3 park theirs in LDS, wave 0 adds
-        f32x4* xch = reinterpret_cast<f32x4*>(smem);
-        constexpr int kHalves = RB > 2 ? 2 : 1;
-        constexpr int kDb = 8 / kHalves;
-        __syncthreads();                     // every wave is done reading its tiles
+        PILLAR_TRACE(20);
+        rows_to_lds<FP8, false>(rk, s_tile, lane);
+        PILLAR_TRACE(21);
+        float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
+        if constexpr (FP8) { half_scales(kv, it, tb, pg, kv.k_scale, ks); half_scales(kv, it, tb, pg, kv.v_scale, vs); }
+        f32x4 s[2][RB];
+        tile_qk_ldsq<RB>(s_tile, s_q, R, s, lane);
+        PILLAR_TRACE(22);
+        // the K rows are consumed: the V rows take their place, and the registers are free for the next tile
+        if (tb + kTileTokens > it.L) zero_tail_rows<FP8>(rv, tb, it.L, geo);
+        rows_to_lds<FP8, true>(rv, s_tile, lane);
+        if (ti + 1 < nt) issue_rows<FP8, true>(kv, it, tb + kTileTokens, pg, geo, rk, rv);
+        PILLAR_TRACE(23);
+        const bool edge = tb + kTileTokens > it.L - n_q;
+        f32x4 tot[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+        bf16x8 p[RB];
 #pragma unroll
-        for (int h = 0; h < kHalves; ++h) {
-          if (wave > 0) {
+        for (int rb = 0; rb < RB; ++rb) {
+          f32x4 pr[2];
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
+          for (int sub = 0; sub < 2; ++sub) {
+            const float sc = c2 * ks[sub];
 #pragma unroll
-              for (int d = 0; d < kDb; ++d) xch[((wave - 1) * RB * kDb + rb * kDb + d) * 64 + lane] = o[rb][h * kDb + d];
+            for (int i = 0; i < 4; ++i) pr[sub][i] = fast_exp2(fmaf(s[sub][rb][i], sc, -lse2[rb]));
           }
-          __syncthreads();
-          if (wave == 0) {
+          if (edge) {
+            const int r = 16 * rb + n;
+            const int last = it.L - n_q + (r < R ? r / G : n_q - 1);
 #pragma unroll
-            for (int w = 0; w < kWaves - 1; ++w)
+            for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-              for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int d = 0; d < kDb; ++d) o[rb][h * kDb + d] += xch[(w * RB * kDb + rb * kDb + d) * 64 + lane];
+              for (int i = 0; i < 4; ++i)
+                if (tb + 16 * sub + 4 * g4 + i > last) pr[sub][i] = 0.f;
           }
-          __syncthreads();                   // LDS free again (next half / next phase's tiles)
+          tot[0] += pr[0];
+          tot[1] += pr[1];
+          if constexpr (FP8) { pr[0] *= vs[0]; pr[1] *= vs[1]; }
+          p[rb] = pack_p(pr[0], pr[1]);
         }
-        PILLAR_TRACE(7);
-        if (wave == 0) {
-          if (pnd.nslices == 1) {
+        if (!(ws.debug & 32))
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-              const int r = 16 * rb + n;
-              if (r < R) {
-                const int i = r / G, hg = r - i * G;
-                uint16_t* dst = out + ((static_cast<int64_t>(pnd.b) * n_q + i) * kv.num_q_heads + pnd.g * G + hg) * kHeadDim;
+        for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
-                for (int db = 0; db < 8; ++db) {
-                  u32x2 pk;
-                  pk.x = pack2(o[rb][db][0], o[rb][db][1]);
-                  pk.y = pack2(o[rb][db][2], o[rb][db][3]);
-                  *reinterpret_cast<u32x2*>(dst + 16 * db + 4 * g4) = pk;
-                }
-              }
+          for (int i = 0; i < 4; ++i) tot[sub][i] = (ws.debug & 64) ? tot[sub][i] : row16_sum(tot[sub][i]) * inv_r;
+          const int tok0 = tb + 16 * sub + 4 * g4;
+          if (n == 0 && !(ws.debug & 128)) {
+            if (tok0 + 3 < it.L) {
+              *reinterpret_cast<f32x4*>(sdst + tok0) = tot[sub];
+            } else {
+#pragma unroll
+              for (int i = 0; i < 4; ++i)
+                if (tok0 + i < it.L) sdst[tok0 + i] = tot[sub][i];
             }
-          } else {
+          }
+        }
+        PILLAR_TRACE(24);
+        tile_pv<RB>(s_tile, p, o, lane);
+        PILLAR_TRACE(25);
+      }
+      PILLAR_TRACE(6);
+      if (it.nslices == 1) {
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-              const int r = 16 * rb + n;
-              if (r < R) {
-                float* dst = ws.part_o + (static_cast<int64_t>(pnd.id) * R + r) * kHeadDim;
-                if (!(ws.debug & 2)) publish_row(dst + 4 * g4, o[rb]);
-              }
-            }
-            wait_stores();
-            int old = 0;
-            if (lane == 0) old = atomicAdd(&ws.cnt2[pnd.pair], 1);
-            old = __builtin_amdgcn_readfirstlane(old);
-            if (old == pnd.nslices - 1) {        // last slice of the pair: O = sum of the slice partials
-              __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-              for (int idx = lane; idx < R * (kHeadDim / 4); idx += 64) {
-                const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-                for (int c = 0; c < pnd.nslices; ++c)
-                  acc += *reinterpret_cast<const f32x4*>(ws.part_o + (static_cast<int64_t>(pnd.first + c) * R + r) * kHeadDim + 4 * d4);
-                const int i = r / G, hg = r - i * G;
-                uint16_t* dst = out + ((static_cast<int64_t>(pnd.b) * n_q + i) * kv.num_q_heads + pnd.g * G + hg) * kHeadDim;
-                u32x2 pk;
-                pk.x = pack2(acc.x, acc.y);
-                pk.y = pack2(acc.z, acc.w);
-                *reinterpret_cast<u32x2*>(dst + 4 * d4) = pk;
-              }
+        for (int rb = 0; rb < RB; ++rb) {
+          const int r = 16 * rb + n;
+          if (r < R) {
+            const int i = r / G, hg = r - i * G;
+            uint16_t* dst = out + ((static_cast<int64_t>(it.b) * n_q + i) * kv.num_q_heads + it.g * G + hg) * kHeadDim;
+#pragma unroll
+            for (int db = 0; db < 8; ++db) {
+              u32x2 pk;
+              pk.x = pack2(o[rb][db][0], o[rb][db][1]);
+              pk.y = pack2(o[rb][db][2], o[rb][db][3]);
+              *reinterpret_cast<u32x2*>(dst + 16 * db + 4 * g4) = pk;
             }
           }
         }
       } else {
-        // the pair never became ready: make the failure visible instead of hanging
-        float* sdst = scores + (static_cast<int64_t>(pnd.b) * kv.num_kv_heads + pnd.g) * score_stride;
-        for (int t = pnd.t_begin + threadIdx.x; t < pnd.t_end; t += kThreads) sdst[t] = __uint_as_float(0x7fc00000u);
-        issue_fetch<FP8>(kv, after, geo, rk, rv);
-        __syncthreads();
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+          const int r = 16 * rb + n;
+          if (r < R && !(ws.debug & 2)) publish_row(ws.part_o + (static_cast<int64_t>(it.id) * R + r) * kHeadDim + 4 * g4, o[rb]);
+        }
+        wait_stores();
+        int old = 0;
+        if (lane == 0) old = atomicAdd(&ws.cnt2[it.pair], 1);
+        old = __builtin_amdgcn_readfirstlane(old);
+        if (old == it.nslices - 1) {             // last slice of the pair: O = sum of the slice partials
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+          for (int idx = lane; idx < R * (kHeadDim / 4); idx += kThreads) {
+            const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+            for (int c = 0; c < it.nslices; ++c)
+              acc += *reinterpret_cast<const f32x4*>(ws.part_o + (static_cast<int64_t>(it.first + c) * R + r) * kHeadDim + 4 * d4);
+            const int i = r / G, hg = r - i * G;
+            uint16_t* dst = out + ((static_cast<int64_t>(it.b) * n_q + i) * kv.num_q_heads + it.g * G + hg) * kHeadDim;
+            u32x2 pk;
+            pk.x = pack2(acc.x, acc.y);
+            pk.y = pack2(acc.z, acc.w);
+            *reinterpret_cast<u32x2*>(dst + 4 * d4) = pk;
+          }
+        }
       }
-      k_ahead = has_nxt;
-      kv_ahead = !has_nxt && has_cur;
     } else {
-      k_ahead = false;
+      // the pair never became ready: make the failure visible instead of hanging
+      if (lane == 0) atomicAdd(&ws.ctrl[2], 1);
+      for (int t = it.t_begin + lane; t < it.t_end; t += kThreads) sdst[t] = __uint_as_float(0x7fc00000u);
     }
-    PILLAR_TRACE(8);
-    pnd = cur;
-    pnd_pg = cur_pg;
-    has_pnd = has_cur;
+    }
+    PILLAR_TRACE(7);
+    prev = cur;
+    prev_pg = cur_pg;
+    has_prev = has_cur;
+    // a ticket is taken only when the wavefront can start on it: a slice reserved early would
+    // hold back the log-sum-exp of its whole pair
+    if (has_cur) {
+      int next_ticket = 0;
+      if (lane == 0) next_ticket = atomicAdd(&ws.ctrl[0], 1);
+      ticket = __builtin_amdgcn_readfirstlane(next_ticket);
+    } else {
+      ticket = total;
+    }
   }
-  if ((ws.debug & 16) && blockIdx.x == 0 && threadIdx.x == 0) ws.trace[0] = tr_n;
+#ifdef PILLAR_TRACING
+  if (blockIdx.x == 0 && threadIdx.x == 0) ws.trace[0] = tr_n;
+#endif
 }
 
 FusedWs carve(const KvView& kv, int n_q, int slice_tokens, void* workspace, size_t* total_bytes) {
@@ -769,26 +680,20 @@ int pick_slice_tokens(const KvView& kv) {
   return s;
 }
 
-int grid_size() { return (options().verify_grid > 0 ? options().verify_grid : 2) * num_cus(); }
+// wavefronts in the persistent grid: what the registers and LDS of this kernel let a compute unit hold
+int grid_size() { return (options().verify_grid > 0 ? options().verify_grid : kWavesPerCu) * num_cus(); }
 
 template <int RB, bool FP8>
 hipError_t run(const VerifyArgs& a, hipStream_t st) {
   const KvView& kv = a.kv;
   const FusedWs ws = carve(kv, a.n_q, pick_slice_tokens(kv), a.workspace, nullptr);
-  static bool attr_done = false;
-  if (!attr_done) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_fused_mfma<RB, FP8>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
   {
     KernelTimer t("verify_fused_plan", st);
     hipLaunchKernelGGL(fused_plan, dim3(1), dim3(1024), 0, st, kv, ws);
   }
   {
     KernelTimer t("verify_fused_mfma", st);
-    hipLaunchKernelGGL((verify_fused_mfma<RB, FP8>), dim3(grid_size()), dim3(kThreads), kLdsBytes, st, kv,
+    hipLaunchKernelGGL((verify_fused_mfma<RB, FP8>), dim3(grid_size()), dim3(kThreads), 0, st, kv,
                        static_cast<const uint16_t*>(a.q), a.n_q, ws, static_cast<uint16_t*>(a.out), a.lse, a.scores,
                        a.score_stride);
   }
@@ -801,8 +706,8 @@ bool verify_fused_supported(const VerifyArgs& a) {
   if (!a.scores || !verify_mfma_supported(a)) return false;
   const KvView& kv = a.kv;
   if (kv.batch > kMaxBatchInLds) return false;
-  // every workgroup can park two slices: a pair must fit in what the resident grid can hold
-  if (slices_of(kv.max_seq_len, pick_slice_tokens(kv)) > grid_size()) return false;
+  // a pair must not be able to occupy every resident wavefront (see the progress argument above)
+  if (slices_of(kv.max_seq_len, pick_slice_tokens(kv)) > grid_size() / 2) return false;
   return true;
 }
 
