@@ -79,6 +79,7 @@ bool force_generic();
 struct Options {
   int verify_chunk = 0;
   int verify_grid = 0;
+  int verify_mode = 0;    // 0: two-pass kernels, 1: single persistent kernel
   int decode_wgs = 0;
   int debug = 0;      // experiment switches, meaning private to the kernels
 };

@@ -262,6 +262,9 @@ int pillar_set_option(const char* name, int64_t value) {
   } else if (k == "verify_grid") {
     if (value > 8) return PILLAR_EINVAL;
     o.verify_grid = static_cast<int>(value);
+  } else if (k == "verify_mode") {
+    if (value > 1) return PILLAR_EINVAL;
+    o.verify_mode = static_cast<int>(value);
   } else if (k == "decode_wgs") {
     if (value > (1 << 20)) return PILLAR_EINVAL;
     o.decode_wgs = static_cast<int>(value);
