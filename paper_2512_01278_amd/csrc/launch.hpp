@@ -68,6 +68,9 @@ bool verify_fused_supported(const VerifyArgs& a);      // needs a.scores
 size_t verify_fused_workspace(const KvView& kv, int n_q);
 size_t verify_fused_trace_offset(const KvView& kv, int n_q);
 hipError_t launch_verify_fused(const VerifyArgs& a, hipStream_t s);
+bool verify_range_supported(const VerifyArgs& a);      // needs a.scores
+size_t verify_range_workspace(const KvView& kv, int n_q);
+hipError_t launch_verify_range(const VerifyArgs& a, hipStream_t s);
 bool decode_mfma_supported(const DecodeArgs& a);
 size_t decode_mfma_workspace(const KvView& kv, int max_budget);
 hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s);
@@ -79,7 +82,7 @@ bool force_generic();
 struct Options {
   int verify_chunk = 0;
   int verify_grid = 0;
-  int verify_mode = 0;    // 0: two-pass kernels, 1: single persistent kernel
+  int verify_mode = 0;    // 0: two passes over equal ranges, 1: single persistent kernel, 2: two passes over fixed slices
   int decode_wgs = 0;
   int debug = 0;      // experiment switches, meaning private to the kernels
 };

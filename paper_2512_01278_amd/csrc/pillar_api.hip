@@ -125,6 +125,8 @@ size_t verify_workspace(const KvView& v, int n_q) {
     b = verify_mfma_workspace(v, n_q);
     const size_t c = verify_fused_workspace(v, n_q);
     if (c > b) b = c;
+    const size_t d = verify_range_workspace(v, n_q);
+    if (d > b) b = d;
   }
   return a > b ? a : b;
 }
@@ -195,7 +197,8 @@ int pillar_verify_attn(const pillar_kv_t* kv, const void* q, int32_t spec_len_k,
   if (rc != PILLAR_OK) return rc;
   const hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
-  if (!force_generic() && verify_fused_supported(a)) e = launch_verify_fused(a, st);
+  if (!force_generic() && options().verify_mode == 0 && verify_range_supported(a)) e = launch_verify_range(a, st);
+  else if (!force_generic() && verify_fused_supported(a)) e = launch_verify_fused(a, st);
   else if (!force_generic() && verify_mfma_supported(a)) e = launch_verify_mfma(a, st);
   else e = launch_verify_generic(a, st);
   return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
@@ -263,7 +266,7 @@ int pillar_set_option(const char* name, int64_t value) {
     if (value > 8) return PILLAR_EINVAL;
     o.verify_grid = static_cast<int>(value);
   } else if (k == "verify_mode") {
-    if (value > 1) return PILLAR_EINVAL;
+    if (value > 2) return PILLAR_EINVAL;
     o.verify_mode = static_cast<int>(value);
   } else if (k == "decode_wgs") {
     if (value > (1 << 20)) return PILLAR_EINVAL;

@@ -1,0 +1,619 @@
+// Verification attention with the score statistic (paper Section 4.1) as two
+// streaming passes over an evenly divided token range.
+//
+// The probability of a token needs the row's log-sum-exp over the WHOLE
+// context, so the context is visited twice:
+//   pass 1 (K only)   S^T = K Q^T on the matrix cores, running (max, sum) per
+//                     row -> one (m, l) per row and segment
+//   combine           per (request, KV head): final log-sum-exp per row
+//   pass 2 (K and V)  p = exp2(s - lse) is the exact probability: the score
+//                     statistic (mean of p over the rows of the GQA group) is
+//                     written directly, and O = sum p V needs no running
+//                     maximum; segment partials of O add linearly
+//   merge             per (request, KV head) cut into several segments: O = sum
+// Kernel boundaries are the only synchronisation.
+//
+// Work division.  The unit of work is a tile of 32 tokens of one (request, KV
+// head) pair; all units are laid out pair-major (request, head, tile) and the
+// T units are cut into N equal contiguous ranges, one per wavefront, N being
+// the number of wavefronts the chip holds at once.  Every wavefront therefore
+// streams the same number of bytes and the grid drains all at once; a fixed
+// slice size instead leaves the last round of workgroups on a half-empty chip
+// (measured: a third of the pass-2 time at batch 128).  A range crosses pair
+// boundaries; the stretch of one pair inside one range is a segment, and the
+// segment of pair p in range w owns partial-result slot p + w (distinct
+// segments have distinct sums because both indices grow along the layout).
+#include "launch.hpp"
+#include "mfma_tile.hpp"
+#include "verify_stream.hpp"
+
+namespace pillar {
+namespace {
+
+constexpr int kThreads = 64;                   // one wavefront per workgroup
+constexpr int kWindowPages = 64;               // page ids held per register: one per lane
+
+struct RangeWs {
+  int32_t* ctrl;        // [0] total units T
+  int32_t* ureq;        // [B+1] first unit of request b (its heads follow each other)
+  float* part_m;        // [pairs + N][rows_pad]  log2 domain
+  float* part_l;        // [pairs + N][rows_pad]
+  float* part_o;        // [pairs + N][R][128]
+  float* lse2;          // [pairs][rows_pad]      log2 domain
+  int32_t rows_pad;     // 16 * row blocks
+  int32_t n_ranges;     // N
+  int32_t debug;
+};
+
+__host__ __device__ inline int tiles_of_len(int len) { return (len + kTileTokens - 1) / kTileTokens; }
+
+// first unit of range w, and the range a unit falls in
+__device__ __forceinline__ int range_begin(int w, int total, int n) { return static_cast<int>(static_cast<int64_t>(w) * total / n); }
+__device__ __forceinline__ int range_of(int unit, int total, int n) {
+  return static_cast<int>(((static_cast<int64_t>(unit) + 1) * n - 1) / total);
+}
+
+// ---------------------------------------------------------------- plan ------
+__global__ __launch_bounds__(1024) void range_plan(KvView kv, RangeWs ws) {
+  __shared__ int32_t scan[1024];
+  __shared__ int32_t carry;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  for (int b0 = 0; b0 < kv.batch; b0 += 1024) {
+    const int b = b0 + threadIdx.x;
+    const int mine = b < kv.batch ? tiles_of_len(kv.seq_lens[b]) * kv.num_kv_heads : 0;
+    scan[threadIdx.x] = mine;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      const int v = threadIdx.x >= o ? scan[threadIdx.x - o] : 0;
+      __syncthreads();
+      scan[threadIdx.x] += v;
+      __syncthreads();
+    }
+    if (b < kv.batch) ws.ureq[b] = carry + scan[threadIdx.x] - mine;
+    __syncthreads();
+    if (threadIdx.x == 1023) carry += scan[1023];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    ws.ureq[kv.batch] = carry;
+    ws.ctrl[0] = carry;
+  }
+}
+
+// ------------------------------------------------------------- helpers ------
+// One stretch of one pair inside one range.
+struct Segment {
+  int b, g, L, tiles, tile0, tile1, pair, slot;
+};
+
+// request whose units contain `unit`: two rounds of 64-way search, the prefix table stays in L2
+__device__ __forceinline__ int find_request(const RangeWs& ws, int batch, int unit, int lane) {
+  int lo = 0, n = batch;                       // answer in [lo, lo + n)
+  while (n > 1) {
+    const int step = (n + kThreads - 1) / kThreads;
+    const int probe = lo + min(lane * step, n - 1);
+    const bool le = ws.ureq[probe] <= unit;    // true for a prefix of the lanes (lane 0 always)
+    const int hits = __popcll(__ballot(le));
+    const int first = lo + min((hits - 1) * step, n - 1);
+    n = min(step, lo + n - first);
+    lo = first;
+  }
+  return __builtin_amdgcn_readfirstlane(lo);
+}
+
+// page ids of the 64-page windows `win` and `win + 1` of a request: lane j holds page 64 * win + j
+struct PageWin {
+  int pg_a, pg_b, win;
+};
+
+__device__ __forceinline__ int load_window(const KvView& kv, int b, int win, int last_page, int lane) {
+  return kv.block_table[static_cast<int64_t>(b) * kv.block_table_stride + min(win * kWindowPages + lane, last_page)];
+}
+
+__device__ __forceinline__ PageWin open_window(const KvView& kv, const Segment& sg, int lane) {
+  const int last_page = (sg.L - 1) >> kv.page_shift;
+  PageWin pw;
+  pw.win = ((sg.tile0 * kTileTokens) >> kv.page_shift) / kWindowPages;
+  pw.pg_a = load_window(kv, sg.b, pw.win, last_page, lane);
+  pw.pg_b = load_window(kv, sg.b, pw.win + 1, last_page, lane);
+  return pw;
+}
+
+// Issues the loads of the tile at token tb (K rows into rk when WITH_K, V rows into rv when
+// WITH_V) and reports the pages of its two 16-token halves.  Tiles are issued in ascending
+// order, so the page window only ever moves forward; a 16-token group lies in one page whose
+// id is wave-uniform, which makes the address a scalar base plus a 32-bit per-lane offset.
+// Groups beyond the end of the sequence read the last page of the request: pages are whole, so
+// the rows exist; the caller masks them.
+template <bool FP8, bool WITH_K, bool WITH_V>
+__device__ __forceinline__ void issue_tile(const KvView& kv, const Segment& sg, int tb, PageWin& pw, const LaneGeom<FP8>& geo,
+                                           int lane, u32x4 (&rk)[TileRegs<FP8>::kLoads], u32x4 (&rv)[TileRegs<FP8>::kLoads],
+                                           int (&pages)[2]) {
+  constexpr int kLoads = TileRegs<FP8>::kLoads;
+  constexpr int kPerGroup = kLoads / 2;
+  const int esz = FP8 ? 1 : 2;
+  const int last_page = (sg.L - 1) >> kv.page_shift;
+#pragma unroll
+  for (int grp = 0; grp < 2; ++grp) {
+    const int tok0 = tb + 16 * grp;
+    const int lp = min(tok0 >> kv.page_shift, last_page);
+    if (lp / kWindowPages > pw.win) {          // wave-uniform
+      pw.pg_a = pw.pg_b;
+      pw.win += 1;
+      pw.pg_b = load_window(kv, sg.b, pw.win + 1, last_page, lane);
+    }
+    const int page = __builtin_amdgcn_readlane(pw.pg_a, lp - pw.win * kWindowPages);
+    pages[grp] = page;
+    const int64_t base = (static_cast<int64_t>(page) * kv.stride_page + static_cast<int64_t>(sg.g) * kv.stride_head +
+                          static_cast<int64_t>(tok0 & (kv.page_size - 1)) * kv.stride_slot) * esz;
+    const char* gk = static_cast<const char*>(kv.k_pool) + base;
+    const char* gv = static_cast<const char*>(kv.v_pool) + base;
+#pragma unroll
+    for (int u = 0; u < kPerGroup; ++u) {
+      const uint32_t off = geo.lane_off + u * geo.row_step;
+      if constexpr (WITH_K) rk[grp * kPerGroup + u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gk + off));
+      if constexpr (WITH_V) rv[grp * kPerGroup + u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gv + off));
+    }
+  }
+}
+
+// fp8: dequantisation scales of the two 16-token halves of a tile
+__device__ __forceinline__ void half_scales(const KvView& kv, int g, const int (&pages)[2], const float* table, float (&sc)[2]) {
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) sc[sub] = table[static_cast<int64_t>(pages[sub]) * kv.num_kv_heads + g];
+}
+
+template <int RB>
+__device__ __forceinline__ void load_q_regs(const KvView& kv, const uint16_t* q, int n_q, int G, int R, const Segment& sg,
+                                            bf16x8 (&qf)[RB][4], int lane) {
+  const int n = lane & 15, g4 = lane >> 4;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int r = 16 * rb + n;
+    const int i = r / G, hg = r - i * G;
+    const uint16_t* row = q + ((static_cast<int64_t>(sg.b) * n_q + i) * kv.num_q_heads + sg.g * G + hg) * kHeadDim;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (r < R) v = *reinterpret_cast<const u32x4*>(row + 32 * s + 8 * g4);
+      qf[rb][s] = as_bf16x8(v);
+    }
+  }
+}
+
+// Walks the segments of range w.  `first` positions the walk (one search); `next` steps to the
+// following pair.  Everything in a Segment is wave-uniform.
+struct RangeWalk {
+  int unit, end, total, w;
+};
+
+__device__ __forceinline__ Segment first_segment(const KvView& kv, const RangeWs& ws, RangeWalk& rw, int lane) {
+  Segment sg;
+  sg.b = find_request(ws, kv.batch, rw.unit, lane);
+  sg.L = __builtin_amdgcn_readfirstlane(kv.seq_lens[sg.b]);
+  sg.tiles = tiles_of_len(sg.L);
+  const int rel = rw.unit - __builtin_amdgcn_readfirstlane(ws.ureq[sg.b]);
+  sg.g = rel / sg.tiles;
+  sg.tile0 = rel - sg.g * sg.tiles;
+  sg.tile1 = min(sg.tiles, sg.tile0 + (rw.end - rw.unit));
+  sg.pair = sg.b * kv.num_kv_heads + sg.g;
+  sg.slot = sg.pair + rw.w;
+  return sg;
+}
+
+__device__ __forceinline__ bool next_segment(const KvView& kv, RangeWalk& rw, Segment& sg) {
+  rw.unit += sg.tile1 - sg.tile0;
+  if (rw.unit >= rw.end) return false;
+  sg.g += 1;
+  if (sg.g == kv.num_kv_heads) {
+    sg.g = 0;
+    sg.b += 1;
+    sg.L = __builtin_amdgcn_readfirstlane(kv.seq_lens[sg.b]);
+    sg.tiles = tiles_of_len(sg.L);
+  }
+  sg.tile0 = 0;
+  sg.tile1 = min(sg.tiles, rw.end - rw.unit);
+  sg.pair = sg.b * kv.num_kv_heads + sg.g;
+  sg.slot = sg.pair + rw.w;
+  return true;
+}
+
+// ---------------------------------------------------------------- pass 1 ----
+template <int RB, bool FP8>
+__global__ __launch_bounds__(kThreads, 2) void verify_lse_range(KvView kv, const uint16_t* q, int n_q, RangeWs ws) {
+  __shared__ __attribute__((aligned(16))) uint8_t s_tile[kKTileBytes];
+  const int lane = threadIdx.x;
+  const int n = lane & 15, g4 = lane >> 4;
+  const int G = kv.num_q_heads / kv.num_kv_heads;
+  const int R = n_q * G;
+  const float c2 = kv.sm_scale * kLog2e;
+  const LaneGeom<FP8> geo = lane_geom<FP8>(kv, lane);
+  constexpr int kLoads = TileRegs<FP8>::kLoads;
+  RangeWalk rw;
+  rw.total = ws.ctrl[0];
+  rw.w = blockIdx.x;
+  rw.unit = range_begin(rw.w, rw.total, ws.n_ranges);
+  rw.end = range_begin(rw.w + 1, rw.total, ws.n_ranges);
+  if (rw.unit >= rw.end) return;
+  Segment sg = first_segment(kv, ws, rw, lane);
+  do {
+    PageWin pw = open_window(kv, sg, lane);
+    const int nt = sg.tile1 - sg.tile0;
+    const int t_begin = sg.tile0 * kTileTokens;
+    // K tiles travel two deep: even tiles through ra, odd tiles through rb_
+    u32x4 ra[kLoads], rb_[kLoads], unused[kLoads];
+    int pa[2], pb[2];
+    issue_tile<FP8, true, false>(kv, sg, t_begin, pw, geo, lane, ra, unused, pa);
+    if (nt > 1) issue_tile<FP8, true, false>(kv, sg, t_begin + kTileTokens, pw, geo, lane, rb_, unused, pb);
+    bf16x8 qf[RB][4];
+    load_q_regs<RB>(kv, q, n_q, G, R, sg, qf, lane);
+    float m_run[RB], l_run[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) { m_run[rb] = -INFINITY; l_run[rb] = 0.f; }
+    auto tile = [&](int ti, u32x4 (&regs)[kLoads], int (&pgs)[2]) {
+      const int tb = t_begin + ti * kTileTokens;
+      rows_to_lds<FP8, false>(regs, s_tile, lane);
+      float ks[2] = {1.f, 1.f};
+      if constexpr (FP8) half_scales(kv, sg.g, pgs, kv.k_scale, ks);
+      if (ti + 2 < nt) issue_tile<FP8, true, false>(kv, sg, tb + 2 * kTileTokens, pw, geo, lane, regs, unused, pgs);
+      f32x4 s[2][RB];
+      tile_qk<RB>(s_tile, qf, s, lane);
+      const bool edge = tb + kTileTokens > sg.L - n_q;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) s[sub][rb] *= c2 * ks[sub];
+        if (edge) {
+          const int r = 16 * rb + n;
+          const int last = sg.L - n_q + (r < R ? r / G : n_q - 1);
+#pragma unroll
+          for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (tb + 16 * sub + 4 * g4 + i > last) s[sub][rb][i] = -INFINITY;
+        }
+        const float mx = fmaxf(fmaxf(fmaxf(s[0][rb][0], s[0][rb][1]), fmaxf(s[0][rb][2], s[0][rb][3])),
+                               fmaxf(fmaxf(s[1][rb][0], s[1][rb][1]), fmaxf(s[1][rb][2], s[1][rb][3])));
+        const float m_new = fmaxf(m_run[rb], mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sum += fast_exp2(s[0][rb][i] - m_use) + fast_exp2(s[1][rb][i] - m_use);
+        l_run[rb] = l_run[rb] * fast_exp2(m_run[rb] - m_use) + sum;
+        m_run[rb] = m_new;
+      }
+    };
+    for (int ti = 0; ti < nt; ti += 2) {
+      tile(ti, ra, pa);
+      if (ti + 1 < nt) tile(ti + 1, rb_, pb);
+    }
+    // the 4 token groups of a row -> the segment's (m, l)
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      float mx = fmaxf(m_run[rb], xor16(m_run[rb]));
+      mx = fmaxf(mx, xor32(mx));
+      const float m_use = (mx == -INFINITY) ? 0.f : mx;
+      float l = l_run[rb] * fast_exp2(m_run[rb] - m_use);
+      l += xor16(l);
+      l += xor32(l);
+      if (g4 == 0) {
+        ws.part_m[static_cast<int64_t>(sg.slot) * (RB * 16) + 16 * rb + n] = mx;
+        ws.part_l[static_cast<int64_t>(sg.slot) * (RB * 16) + 16 * rb + n] = l;
+      }
+    }
+  } while (next_segment(kv, rw, sg));
+}
+
+// ---------------------------------------------------------------- combine ---
+// one thread per (pair, padded row)
+__global__ __launch_bounds__(256) void verify_lse_combine_range(KvView kv, int n_q, RangeWs ws, float* lse_out) {
+  const int rows = ws.rows_pad;
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int pairs = kv.batch * kv.num_kv_heads;
+  if (idx >= pairs * rows) return;
+  const int pair = idx / rows, row = idx - pair * rows;
+  const int b = pair / kv.num_kv_heads, g = pair - b * kv.num_kv_heads;
+  const int G = kv.num_q_heads / kv.num_kv_heads;
+  const int R = n_q * G;
+  const int total = ws.ctrl[0];
+  const int tiles = tiles_of_len(kv.seq_lens[b]);
+  const int u0 = ws.ureq[b] + g * tiles;
+  const int w0 = range_of(u0, total, ws.n_ranges), w1 = range_of(u0 + tiles - 1, total, ws.n_ranges);
+  const float* pm = ws.part_m + static_cast<int64_t>(pair + w0) * rows + row;
+  const float* pl = ws.part_l + static_cast<int64_t>(pair + w0) * rows + row;
+  float m = -INFINITY, l = 0.f;
+  for (int c = 0; c <= w1 - w0; ++c) {
+    // with fewer units than ranges some ranges are empty and own no segment
+    if (range_begin(w0 + c, total, ws.n_ranges) == range_begin(w0 + c + 1, total, ws.n_ranges)) continue;
+    const float mc = pm[static_cast<int64_t>(c) * rows], lc = pl[static_cast<int64_t>(c) * rows];
+    const float mn = fmaxf(m, mc);
+    const float mu = (mn == -INFINITY) ? 0.f : mn;
+    l = l * fast_exp2(m - mu) + lc * fast_exp2(mc - mu);
+    m = mn;
+  }
+  // rows beyond R get +inf so that their probabilities vanish in the second pass
+  const float v = row < R ? m + log2f(l) : INFINITY;
+  ws.lse2[idx] = v;
+  if (lse_out && row < R) {
+    const int i = row / G, hg = row - i * G;
+    lse_out[(static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg] = v * kLn2;
+  }
+}
+
+// ---------------------------------------------------------------- pass 2 ----
+template <int RB, bool FP8>
+__global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_score_range(KvView kv, const uint16_t* q, int n_q, RangeWs ws,
+                                                                                 uint16_t* out, float* scores, int64_t score_stride) {
+  // one tile buffer: the K rows, then (once S^T is done) the V rows of the same tile
+  __shared__ __attribute__((aligned(16))) uint8_t s_tile[kVTileBytes];
+  __shared__ __attribute__((aligned(16))) uint8_t s_q[(RB * 16 + 1) * kKRow];
+  const int lane = threadIdx.x;
+  const int n = lane & 15, g4 = lane >> 4;
+  const int G = kv.num_q_heads / kv.num_kv_heads;
+  const int R = n_q * G;
+  const float c2 = kv.sm_scale * kLog2e;
+  const float inv_r = 1.0f / static_cast<float>(R);
+  const LaneGeom<FP8> geo = lane_geom<FP8>(kv, lane);
+  constexpr int kLoads = TileRegs<FP8>::kLoads;
+  constexpr int kQIters = ((RB * 16 + 1) * 16 + kThreads - 1) / kThreads;
+  RangeWalk rw;
+  rw.total = ws.ctrl[0];
+  rw.w = blockIdx.x;
+  rw.unit = range_begin(rw.w, rw.total, ws.n_ranges);
+  rw.end = range_begin(rw.w + 1, rw.total, ws.n_ranges);
+  if (rw.unit >= rw.end) return;
+  Segment sg = first_segment(kv, ws, rw, lane);
+  do {
+    PageWin pw = open_window(kv, sg, lane);
+    const int nt = sg.tile1 - sg.tile0;
+    const int t_begin = sg.tile0 * kTileTokens;
+    u32x4 rk[kLoads], rv[kLoads];
+    int pgs[2], pgs_next[2];
+    issue_tile<FP8, true, true>(kv, sg, t_begin, pw, geo, lane, rk, rv, pgs);
+    {                                          // Q rows of the pair -> LDS (row R is the zero row of the padding)
+      u32x4 qtmp[kQIters];
+#pragma unroll
+      for (int j = 0; j < kQIters; ++j) {
+        const int ch = lane + kThreads * j;
+        const int r = ch >> 4, c = ch & 15;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (r < R) {
+          const int i = r / G, hg = r - i * G;
+          v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(sg.b) * n_q + i) * kv.num_q_heads + sg.g * G + hg) * kHeadDim + 8 * c);
+        }
+        qtmp[j] = v;
+      }
+#pragma unroll
+      for (int j = 0; j < kQIters; ++j) {
+        const int ch = lane + kThreads * j;
+        if (ch < (R + 1) * 16) *reinterpret_cast<u32x4*>(s_q + k_lds_addr(ch >> 4, ch & 15)) = qtmp[j];
+      }
+    }
+    float lse2[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) lse2[rb] = ws.lse2[static_cast<int64_t>(sg.pair) * (RB * 16) + 16 * rb + n];
+    float* sdst = scores + (static_cast<int64_t>(sg.b) * kv.num_kv_heads + sg.g) * score_stride;
+    f32x4 o[RB][8];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int d = 0; d < 8; ++d) o[rb][d] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int ti = 0; ti < nt; ++ti) {
+      const int tb = t_begin + ti * kTileTokens;
+      rows_to_lds<FP8, false>(rk, s_tile, lane);
+      // each register set goes back on the road as soon as its rows are in LDS
+      if (ti + 1 < nt) issue_tile<FP8, true, false>(kv, sg, tb + kTileTokens, pw, geo, lane, rk, rv, pgs_next);
+      float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
+      if constexpr (FP8) { half_scales(kv, sg.g, pgs, kv.k_scale, ks); half_scales(kv, sg.g, pgs, kv.v_scale, vs); }
+      f32x4 s[2][RB];
+      tile_qk_ldsq<RB>(s_tile, s_q, R, s, lane);
+      // the K rows are consumed: the V rows take their place
+      if (tb + kTileTokens > sg.L) zero_tail_rows<FP8>(rv, tb, sg.L, geo);
+      rows_to_lds<FP8, true>(rv, s_tile, lane);
+      if (ti + 1 < nt) {
+        int same[2];
+        issue_tile<FP8, false, true>(kv, sg, tb + kTileTokens, pw, geo, lane, rk, rv, same);
+        pgs[0] = pgs_next[0];
+        pgs[1] = pgs_next[1];
+      }
+      const bool edge = tb + kTileTokens > sg.L - n_q;
+      f32x4 tot[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+      bf16x8 p[RB];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        f32x4 pr[2];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+          const float sc = c2 * ks[sub];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) pr[sub][i] = fast_exp2(fmaf(s[sub][rb][i], sc, -lse2[rb]));
+        }
+        if (edge) {
+          const int r = 16 * rb + n;
+          const int last = sg.L - n_q + (r < R ? r / G : n_q - 1);
+#pragma unroll
+          for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (tb + 16 * sub + 4 * g4 + i > last) pr[sub][i] = 0.f;
+        }
+        tot[0] += pr[0];
+        tot[1] += pr[1];
+        if constexpr (FP8) { pr[0] *= vs[0]; pr[1] *= vs[1]; }
+        p[rb] = pack_p(pr[0], pr[1]);
+      }
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tot[sub][i] = row16_sum(tot[sub][i]) * inv_r;
+        const int tok0 = tb + 16 * sub + 4 * g4;
+        if (n == 0) {
+          if (tok0 + 3 < sg.L) {
+            *reinterpret_cast<f32x4*>(sdst + tok0) = tot[sub];
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (tok0 + i < sg.L) sdst[tok0 + i] = tot[sub][i];
+          }
+        }
+      }
+      tile_pv<RB>(s_tile, p, o, lane);
+    }
+    const bool whole = sg.tile0 == 0 && sg.tile1 == sg.tiles;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const int r = 16 * rb + n;
+      if (r >= R) continue;
+      if (whole) {
+        const int i = r / G, hg = r - i * G;
+        uint16_t* dst = out + ((static_cast<int64_t>(sg.b) * n_q + i) * kv.num_q_heads + sg.g * G + hg) * kHeadDim;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+          u32x2 pk;
+          pk.x = pack2(o[rb][db][0], o[rb][db][1]);
+          pk.y = pack2(o[rb][db][2], o[rb][db][3]);
+          *reinterpret_cast<u32x2*>(dst + 16 * db + 4 * g4) = pk;
+        }
+      } else {
+        float* dst = ws.part_o + (static_cast<int64_t>(sg.slot) * R + r) * kHeadDim + 4 * g4;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + 16 * db) = o[rb][db];
+      }
+    }
+  } while (next_segment(kv, rw, sg));
+}
+
+// ---------------------------------------------------------------- merge -----
+// one workgroup per pair; a pair inside one range was written by pass 2 itself
+__global__ __launch_bounds__(256) void verify_o_merge_range(KvView kv, int n_q, RangeWs ws, uint16_t* out) {
+  const int pair = blockIdx.x;
+  const int b = pair / kv.num_kv_heads, g = pair - b * kv.num_kv_heads;
+  const int G = kv.num_q_heads / kv.num_kv_heads;
+  const int R = n_q * G;
+  const int total = ws.ctrl[0];
+  const int tiles = tiles_of_len(kv.seq_lens[b]);
+  const int u0 = ws.ureq[b] + g * tiles;
+  const int w0 = range_of(u0, total, ws.n_ranges), w1 = range_of(u0 + tiles - 1, total, ws.n_ranges);
+  if (w1 == w0) return;
+  for (int idx = threadIdx.x; idx < R * (kHeadDim / 4); idx += 256) {
+    const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int w = w0; w <= w1; ++w) {
+      if (range_begin(w, total, ws.n_ranges) == range_begin(w + 1, total, ws.n_ranges)) continue;   // empty range
+      acc += *reinterpret_cast<const f32x4*>(ws.part_o + (static_cast<int64_t>(pair + w) * R + r) * kHeadDim + 4 * d4);
+    }
+    const int i = r / G, hg = r - i * G;
+    uint16_t* dst = out + ((static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg) * kHeadDim;
+    u32x2 pk;
+    pk.x = pack2(acc.x, acc.y);
+    pk.y = pack2(acc.z, acc.w);
+    *reinterpret_cast<u32x2*>(dst + 4 * d4) = pk;
+  }
+}
+
+// ---------------------------------------------------------------- host ------
+int num_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    cus = v;
+  }
+  return cus;
+}
+
+// wavefronts of pass 2 a compute unit holds at once (registers: 2 per SIMD up to 32 rows, else 1; LDS allows as many)
+int ranges_for(int rb) {
+  const int per_cu = rb >= 3 ? 4 : 8;
+  const int opt = options().verify_grid;
+  return (opt > 0 ? opt : per_cu) * num_cus();
+}
+
+int row_blocks(const KvView& kv, int n_q) { return (n_q * (kv.num_q_heads / kv.num_kv_heads) + 15) / 16; }
+
+RangeWs carve(const KvView& kv, int n_q, void* workspace, size_t* total_bytes) {
+  const int G = kv.num_q_heads / kv.num_kv_heads;
+  const size_t R = static_cast<size_t>(n_q) * G;
+  const size_t rpad = (R + 15) / 16 * 16;
+  const size_t pairs = static_cast<size_t>(kv.batch) * kv.num_kv_heads;
+  const size_t n = static_cast<size_t>(ranges_for(static_cast<int>(rpad / 16)));
+  const size_t slots = pairs + n;
+  char* p = static_cast<char*>(workspace);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { char* r = p ? p + off : nullptr; off += align_up(bytes, 256); return r; };
+  RangeWs w;
+  w.ctrl = reinterpret_cast<int32_t*>(take(64 * 4));
+  w.ureq = reinterpret_cast<int32_t*>(take((static_cast<size_t>(kv.batch) + 1) * 4));
+  w.part_m = reinterpret_cast<float*>(take(slots * rpad * 4));
+  w.part_l = reinterpret_cast<float*>(take(slots * rpad * 4));
+  w.part_o = reinterpret_cast<float*>(take(slots * R * kHeadDim * 4));
+  w.lse2 = reinterpret_cast<float*>(take(pairs * rpad * 4));
+  w.rows_pad = static_cast<int32_t>(rpad);
+  w.n_ranges = static_cast<int32_t>(n);
+  w.debug = options().debug;
+  if (total_bytes) *total_bytes = off;
+  return w;
+}
+
+template <int RB, bool FP8>
+hipError_t run(const VerifyArgs& a, hipStream_t st) {
+  const KvView& kv = a.kv;
+  const RangeWs ws = carve(kv, a.n_q, a.workspace, nullptr);
+  const uint16_t* q = static_cast<const uint16_t*>(a.q);
+  uint16_t* out = static_cast<uint16_t*>(a.out);
+  const int pairs = kv.batch * kv.num_kv_heads;
+  {
+    KernelTimer t("verify_range_plan", st);
+    hipLaunchKernelGGL(range_plan, dim3(1), dim3(1024), 0, st, kv, ws);
+  }
+  {
+    KernelTimer t("verify_lse_range", st);
+    hipLaunchKernelGGL((verify_lse_range<RB, FP8>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws);
+  }
+  {
+    KernelTimer t("verify_lse_combine", st);
+    hipLaunchKernelGGL(verify_lse_combine_range, dim3((pairs * ws.rows_pad + 255) / 256), dim3(256), 0, st, kv, a.n_q, ws, a.lse);
+  }
+  {
+    KernelTimer t("verify_score_range", st);
+    hipLaunchKernelGGL((verify_score_range<RB, FP8>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out, a.scores,
+                       a.score_stride);
+  }
+  {
+    KernelTimer t("verify_o_merge", st);
+    hipLaunchKernelGGL(verify_o_merge_range, dim3(pairs), dim3(256), 0, st, kv, a.n_q, ws, out);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool verify_range_supported(const VerifyArgs& a) {
+  if (!a.scores || !verify_mfma_supported(a)) return false;
+  // units are counted in 32 bits
+  const int64_t units = static_cast<int64_t>(a.kv.batch) * a.kv.num_kv_heads * tiles_of_len(a.kv.max_seq_len);
+  return units < (int64_t{1} << 30) && (a.score_stride % 4 == 0);
+}
+
+size_t verify_range_workspace(const KvView& kv, int n_q) {
+  size_t total = 0;
+  carve(kv, n_q, nullptr, &total);
+  return total;
+}
+
+hipError_t launch_verify_range(const VerifyArgs& a, hipStream_t s) {
+  const int rb = row_blocks(a.kv, a.n_q);
+  const bool fp8 = a.kv_dtype == PILLAR_FP8_E4M3;
+#define PILLAR_CASE(N) \
+  if (rb == N) return fp8 ? run<N, true>(a, s) : run<N, false>(a, s);
+  PILLAR_CASE(1)
+  PILLAR_CASE(2)
+  PILLAR_CASE(3)
+  PILLAR_CASE(4)
+#undef PILLAR_CASE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace pillar
