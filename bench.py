@@ -98,9 +98,7 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
 
-    # timed region: exactly `steps` steps, per-kernel HIP events inside the library
-    pa.pillar_profile_reset()
-    pa.pillar_profile_enable(True)
+    # timed region: exactly `steps` steps, nothing but the three entry points between the clocks
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -111,6 +109,17 @@ def main() -> int:
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     gpu_ms = ev0.elapsed_time(ev1)
+
+    # the same `steps` steps again with a HIP event pair around every kernel (recorded by the
+    # library on the launch stream): per-kernel durations; the events themselves stretch the step
+    pa.pillar_profile_reset()
+    pa.pillar_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof_wall_ms = (time.perf_counter() - t0) * 1e3
     pa.pillar_profile_enable(False)
     prof = pa.pillar_profile_read()
 
@@ -148,6 +157,7 @@ def main() -> int:
                    "selected_rows": w.selected_rows(), "truncated": args.batch is not None},
         "tokens_per_s": round(q_tokens / (ms_per_step * 1e-3), 1),
         "gpu_ms_per_step": round(gpu_ms / args.steps, 5),
+        "ms_per_step_with_kernel_events": round(prof_wall_ms / args.steps, 5),
         "stage_us": {k: round(v, 2) for k, v in stage_us.items()},
         "stage_gbps": {"verify": round(verify_gbps, 1), "draft": round(draft_gbps, 1), "step": round(step_gbps, 1)},
         "stage_frac_of_peak": {"verify": round(verify_gbps / HBM_PEAK_GBPS, 4),
@@ -155,13 +165,17 @@ def main() -> int:
                                "step": round(step_gbps / HBM_PEAK_GBPS, 4)},
         "algorithmic_bytes": {"verify": vb, "topk": tb, "draft": db},
         "kernels": kern,
-        "roofline": {"bound": "hbm", "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "kernel": dom, "avg_us": round(dom_us, 2), "algorithmic_bytes": dom_bytes,
-                     "note": "dominant kernel of the step: the algorithmic bytes of its stage (verify: every KV "
-                             "row once + one fp32 score per token and KV head + Q and O) over its average "
-                             "launch duration, HIP events on the launch stream inside the timed region; "
-                             "stage_gbps divides the same bytes by ALL kernels of the stage"},
+        "roofline": {"bound": "hbm", "achieved": round(verify_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(verify_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": "verification stage = " + " + ".join(sorted(k for k in prof if k.startswith("verify"))),
+                     "avg_us": round(stage_us["verify"], 2), "algorithmic_bytes": vb,
+                     "dominant_kernel": {"name": dom, "avg_us": round(dom_us, 2), "achieved": round(dom_gbps, 1),
+                                         "frac": round(dom_gbps / HBM_PEAK_GBPS, 4)},
+                     "note": "algorithmic bytes of the verification stage (every KV row once + one fp32 score per "
+                             "token and KV head + Q and O) over the SUM of the average durations of all its kernels "
+                             "(HIP events on the launch stream): the method needs the log-sum-exp pass as much as the "
+                             "score pass, so the stage, not its longest kernel, is priced against the roofline; "
+                             "dominant_kernel prices the same bytes against the longest kernel alone"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

@@ -70,6 +70,7 @@ size_t verify_fused_trace_offset(const KvView& kv, int n_q);
 hipError_t launch_verify_fused(const VerifyArgs& a, hipStream_t s);
 bool verify_range_supported(const VerifyArgs& a);      // needs a.scores
 size_t verify_range_workspace(const KvView& kv, int n_q);
+size_t verify_range_trace_offset(const KvView& kv, int n_q);
 hipError_t launch_verify_range(const VerifyArgs& a, hipStream_t s);
 bool decode_mfma_supported(const DecodeArgs& a);
 size_t decode_mfma_workspace(const KvView& kv, int max_budget);

@@ -282,6 +282,7 @@ int pillar_set_option(const char* name, int64_t value) {
 // debugging aid (not part of the documented ABI): byte offset of the timestamp trace in the workspace
 size_t pillar_debug_trace_offset(const pillar_kv_t* kv, int32_t spec_len_k) {
   if (check_kv(kv) != PILLAR_OK) return 0;
+  if (options().verify_mode == 0) return verify_range_trace_offset(make_view(kv), spec_len_k + 1);
   return verify_fused_trace_offset(make_view(kv), spec_len_k + 1);
 }
 

@@ -43,6 +43,7 @@ struct RangeWs {
   int32_t rows_pad;     // 16 * row blocks
   int32_t n_ranges;     // N
   int32_t debug;
+  long long* trace;     // [8192] timestamps (tracing builds only)
 };
 
 __host__ __device__ inline int tiles_of_len(int len) { return (len + kTileTokens - 1) / kTileTokens; }
@@ -107,18 +108,7 @@ struct PageWin {
   int pg_a, pg_b, win;
 };
 
-__device__ __forceinline__ int load_window(const KvView& kv, int b, int win, int last_page, int lane) {
-  return kv.block_table[static_cast<int64_t>(b) * kv.block_table_stride + min(win * kWindowPages + lane, last_page)];
-}
-
-__device__ __forceinline__ PageWin open_window(const KvView& kv, const Segment& sg, int lane) {
-  const int last_page = (sg.L - 1) >> kv.page_shift;
-  PageWin pw;
-  pw.win = ((sg.tile0 * kTileTokens) >> kv.page_shift) / kWindowPages;
-  pw.pg_a = load_window(kv, sg.b, pw.win, last_page, lane);
-  pw.pg_b = load_window(kv, sg.b, pw.win + 1, last_page, lane);
-  return pw;
-}
+__device__ __forceinline__ int load_window(const KvView& kv, int b, int win, int lane);
 
 // Issues the loads of the tile at token tb (K rows into rk when WITH_K, V rows into rv when
 // WITH_V) and reports the pages of its two 16-token halves.  Tiles are issued in ascending
@@ -141,7 +131,7 @@ __device__ __forceinline__ void issue_tile(const KvView& kv, const Segment& sg, 
     if (lp / kWindowPages > pw.win) {          // wave-uniform
       pw.pg_a = pw.pg_b;
       pw.win += 1;
-      pw.pg_b = load_window(kv, sg.b, pw.win + 1, last_page, lane);
+      pw.pg_b = load_window(kv, sg.b, pw.win + 1, lane);
     }
     const int page = __builtin_amdgcn_readlane(pw.pg_a, lp - pw.win * kWindowPages);
     pages[grp] = page;
@@ -182,41 +172,121 @@ __device__ __forceinline__ void load_q_regs(const KvView& kv, const uint16_t* q,
   }
 }
 
-// Walks the segments of range w.  `first` positions the walk (one search); `next` steps to the
-// following pair.  Everything in a Segment is wave-uniform.
-struct RangeWalk {
-  int unit, end, total, w;
+// A tile on its way from HBM to a register set: which segment it belongs to and where it starts.
+struct Flight {
+  Segment sg;
+  int tb;            // first token of the tile
+  int pages[2];      // pages of its two 16-token halves
+  bool valid;
 };
 
-__device__ __forceinline__ Segment first_segment(const KvView& kv, const RangeWs& ws, RangeWalk& rw, int lane) {
-  Segment sg;
-  sg.b = find_request(ws, kv.batch, rw.unit, lane);
-  sg.L = __builtin_amdgcn_readfirstlane(kv.seq_lens[sg.b]);
-  sg.tiles = tiles_of_len(sg.L);
-  const int rel = rw.unit - __builtin_amdgcn_readfirstlane(ws.ureq[sg.b]);
-  sg.g = rel / sg.tiles;
-  sg.tile0 = rel - sg.g * sg.tiles;
-  sg.tile1 = min(sg.tiles, sg.tile0 + (rw.end - rw.unit));
-  sg.pair = sg.b * kv.num_kv_heads + sg.g;
-  sg.slot = sg.pair + rw.w;
-  return sg;
+// Issue side of the tile stream of one range.  The stream runs ahead of the arithmetic by the
+// tiles in flight and crosses pair boundaries without draining: when it enters a pair it already
+// holds the page ids of the pair after it (they were fetched one pair earlier).
+struct Cursor {
+  int unit, end, w;  // next unit to issue, end of the range, index of the range
+  Segment sg;        // the segment that unit belongs to
+  int tile;          // next tile of sg
+  PageWin pw;
+  int pg_next;       // page window 0 of the request of the following pair
+  int len_next;      // sequence length of that request (per-lane copy)
+  bool live;
+};
+
+__device__ __forceinline__ int load_window(const KvView& kv, int b, int win, int lane) {
+  // entries past the last page of the request are never used as addresses (issue_tile clamps), so
+  // it is enough to stay inside the table row
+  return kv.block_table[static_cast<int64_t>(b) * kv.block_table_stride + min(win * kWindowPages + lane, kv.block_table_stride - 1)];
 }
 
-__device__ __forceinline__ bool next_segment(const KvView& kv, RangeWalk& rw, Segment& sg) {
-  rw.unit += sg.tile1 - sg.tile0;
-  if (rw.unit >= rw.end) return false;
-  sg.g += 1;
-  if (sg.g == kv.num_kv_heads) {
-    sg.g = 0;
-    sg.b += 1;
-    sg.L = __builtin_amdgcn_readfirstlane(kv.seq_lens[sg.b]);
-    sg.tiles = tiles_of_len(sg.L);
-  }
-  sg.tile0 = 0;
-  sg.tile1 = min(sg.tiles, rw.end - rw.unit);
+__device__ __forceinline__ void prefetch_following(const KvView& kv, Cursor& c, int lane) {
+  int nb = c.sg.b + (c.sg.g + 1 == kv.num_kv_heads ? 1 : 0);
+  nb = min(nb, kv.batch - 1);                  // past the last request nothing of this is used
+  c.len_next = kv.seq_lens[nb];
+  c.pg_next = load_window(kv, nb, 0, lane);
+}
+
+__device__ __forceinline__ Segment uniform(const Segment& s) {
+  Segment u;
+  u.b = __builtin_amdgcn_readfirstlane(s.b);
+  u.g = __builtin_amdgcn_readfirstlane(s.g);
+  u.L = __builtin_amdgcn_readfirstlane(s.L);
+  u.tiles = __builtin_amdgcn_readfirstlane(s.tiles);
+  u.tile0 = __builtin_amdgcn_readfirstlane(s.tile0);
+  u.tile1 = __builtin_amdgcn_readfirstlane(s.tile1);
+  u.pair = __builtin_amdgcn_readfirstlane(s.pair);
+  u.slot = __builtin_amdgcn_readfirstlane(s.slot);
+  return u;
+}
+
+__device__ __forceinline__ Cursor open_cursor(const KvView& kv, const RangeWs& ws, int lane) {
+  Cursor c;
+  const int total = ws.ctrl[0];
+  c.w = blockIdx.x;
+  c.unit = range_begin(c.w, total, ws.n_ranges);
+  c.end = range_begin(c.w + 1, total, ws.n_ranges);
+  c.live = c.unit < c.end;
+  c.sg = Segment{};
+  c.tile = 0;
+  c.pw = PageWin{};
+  c.pg_next = 0;
+  c.len_next = 0;
+  if (!c.live) return c;
+  Segment sg;
+  sg.b = find_request(ws, kv.batch, c.unit, lane);
+  sg.L = __builtin_amdgcn_readfirstlane(kv.seq_lens[sg.b]);
+  sg.tiles = tiles_of_len(sg.L);
+  const int rel = c.unit - __builtin_amdgcn_readfirstlane(ws.ureq[sg.b]);
+  sg.g = rel / sg.tiles;
+  sg.tile0 = rel - sg.g * sg.tiles;
+  sg.tile1 = min(sg.tiles, sg.tile0 + (c.end - c.unit));
   sg.pair = sg.b * kv.num_kv_heads + sg.g;
-  sg.slot = sg.pair + rw.w;
-  return true;
+  sg.slot = sg.pair + c.w;
+  c.sg = sg;
+  c.tile = sg.tile0;
+  c.pw.win = ((sg.tile0 * kTileTokens) >> kv.page_shift) / kWindowPages;
+  c.pw.pg_a = load_window(kv, sg.b, c.pw.win, lane);
+  c.pw.pg_b = load_window(kv, sg.b, c.pw.win + 1, lane);
+  prefetch_following(kv, c, lane);
+  return c;
+}
+
+// Issues the next tile of the stream into a register set and steps the cursor.
+template <bool FP8, bool WITH_V>
+__device__ __forceinline__ Flight issue_next(const KvView& kv, Cursor& c, const LaneGeom<FP8>& geo, int lane,
+                                             u32x4 (&rk)[TileRegs<FP8>::kLoads], u32x4 (&rv)[TileRegs<FP8>::kLoads]) {
+  Flight f;
+  f.valid = c.live;
+  f.sg = c.sg;
+  f.tb = c.tile * kTileTokens;
+  f.pages[0] = f.pages[1] = 0;
+  if (!c.live) return f;
+  issue_tile<FP8, true, WITH_V>(kv, c.sg, f.tb, c.pw, geo, lane, rk, rv, f.pages);
+  c.tile += 1;
+  c.unit += 1;
+  if (c.unit >= c.end) {
+    c.live = false;
+  } else if (c.tile == c.sg.tile1) {           // on to the next pair
+    Segment sg = c.sg;
+    sg.g += 1;
+    if (sg.g == kv.num_kv_heads) {
+      sg.g = 0;
+      sg.b += 1;
+    }
+    sg.L = __builtin_amdgcn_readfirstlane(c.len_next);
+    sg.tiles = tiles_of_len(sg.L);
+    sg.tile0 = 0;
+    sg.tile1 = min(sg.tiles, c.end - c.unit);
+    sg.pair = sg.b * kv.num_kv_heads + sg.g;
+    sg.slot = sg.pair + c.w;
+    c.sg = uniform(sg);
+    c.tile = 0;
+    c.pw.win = 0;
+    c.pw.pg_a = c.pg_next;
+    c.pw.pg_b = load_window(kv, c.sg.b, 1, lane);
+    prefetch_following(kv, c, lane);
+  }
+  return f;
 }
 
 // ---------------------------------------------------------------- pass 1 ----
@@ -230,65 +300,17 @@ __global__ __launch_bounds__(kThreads, 2) void verify_lse_range(KvView kv, const
   const float c2 = kv.sm_scale * kLog2e;
   const LaneGeom<FP8> geo = lane_geom<FP8>(kv, lane);
   constexpr int kLoads = TileRegs<FP8>::kLoads;
-  RangeWalk rw;
-  rw.total = ws.ctrl[0];
-  rw.w = blockIdx.x;
-  rw.unit = range_begin(rw.w, rw.total, ws.n_ranges);
-  rw.end = range_begin(rw.w + 1, rw.total, ws.n_ranges);
-  if (rw.unit >= rw.end) return;
-  Segment sg = first_segment(kv, ws, rw, lane);
-  do {
-    PageWin pw = open_window(kv, sg, lane);
-    const int nt = sg.tile1 - sg.tile0;
-    const int t_begin = sg.tile0 * kTileTokens;
-    // K tiles travel two deep: even tiles through ra, odd tiles through rb_
-    u32x4 ra[kLoads], rb_[kLoads], unused[kLoads];
-    int pa[2], pb[2];
-    issue_tile<FP8, true, false>(kv, sg, t_begin, pw, geo, lane, ra, unused, pa);
-    if (nt > 1) issue_tile<FP8, true, false>(kv, sg, t_begin + kTileTokens, pw, geo, lane, rb_, unused, pb);
-    bf16x8 qf[RB][4];
-    load_q_regs<RB>(kv, q, n_q, G, R, sg, qf, lane);
-    float m_run[RB], l_run[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) { m_run[rb] = -INFINITY; l_run[rb] = 0.f; }
-    auto tile = [&](int ti, u32x4 (&regs)[kLoads], int (&pgs)[2]) {
-      const int tb = t_begin + ti * kTileTokens;
-      rows_to_lds<FP8, false>(regs, s_tile, lane);
-      float ks[2] = {1.f, 1.f};
-      if constexpr (FP8) half_scales(kv, sg.g, pgs, kv.k_scale, ks);
-      if (ti + 2 < nt) issue_tile<FP8, true, false>(kv, sg, tb + 2 * kTileTokens, pw, geo, lane, regs, unused, pgs);
-      f32x4 s[2][RB];
-      tile_qk<RB>(s_tile, qf, s, lane);
-      const bool edge = tb + kTileTokens > sg.L - n_q;
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) s[sub][rb] *= c2 * ks[sub];
-        if (edge) {
-          const int r = 16 * rb + n;
-          const int last = sg.L - n_q + (r < R ? r / G : n_q - 1);
-#pragma unroll
-          for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (tb + 16 * sub + 4 * g4 + i > last) s[sub][rb][i] = -INFINITY;
-        }
-        const float mx = fmaxf(fmaxf(fmaxf(s[0][rb][0], s[0][rb][1]), fmaxf(s[0][rb][2], s[0][rb][3])),
-                               fmaxf(fmaxf(s[1][rb][0], s[1][rb][1]), fmaxf(s[1][rb][2], s[1][rb][3])));
-        const float m_new = fmaxf(m_run[rb], mx);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        float sum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sum += fast_exp2(s[0][rb][i] - m_use) + fast_exp2(s[1][rb][i] - m_use);
-        l_run[rb] = l_run[rb] * fast_exp2(m_run[rb] - m_use) + sum;
-        m_run[rb] = m_new;
-      }
-    };
-    for (int ti = 0; ti < nt; ti += 2) {
-      tile(ti, ra, pa);
-      if (ti + 1 < nt) tile(ti + 1, rb_, pb);
-    }
-    // the 4 token groups of a row -> the segment's (m, l)
+  Cursor cur = open_cursor(kv, ws, lane);
+  if (!cur.live) return;
+  // K tiles travel two deep: even tiles through ra, odd tiles through rb_
+  u32x4 ra[kLoads], rb_[kLoads], unused[kLoads];
+  Flight fa = issue_next<FP8, false>(kv, cur, geo, lane, ra, unused);
+  Flight fb = issue_next<FP8, false>(kv, cur, geo, lane, rb_, unused);
+  Segment cs = fa.sg;
+  bool started = false;
+  bf16x8 qf[RB][4];
+  float m_run[RB], l_run[RB];
+  auto finish = [&]() {                        // the 4 token groups of a row -> the segment's (m, l)
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       float mx = fmaxf(m_run[rb], xor16(m_run[rb]));
@@ -298,11 +320,59 @@ __global__ __launch_bounds__(kThreads, 2) void verify_lse_range(KvView kv, const
       l += xor16(l);
       l += xor32(l);
       if (g4 == 0) {
-        ws.part_m[static_cast<int64_t>(sg.slot) * (RB * 16) + 16 * rb + n] = mx;
-        ws.part_l[static_cast<int64_t>(sg.slot) * (RB * 16) + 16 * rb + n] = l;
+        ws.part_m[static_cast<int64_t>(cs.slot) * (RB * 16) + 16 * rb + n] = mx;
+        ws.part_l[static_cast<int64_t>(cs.slot) * (RB * 16) + 16 * rb + n] = l;
       }
     }
-  } while (next_segment(kv, rw, sg));
+  };
+  auto tile = [&](Flight& f, u32x4 (&regs)[kLoads]) {
+    if (!started || f.sg.slot != cs.slot) {    // wave-uniform: the stream has entered another pair
+      if (started) finish();
+      cs = f.sg;
+      started = true;
+      load_q_regs<RB>(kv, q, n_q, G, R, cs, qf, lane);
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) { m_run[rb] = -INFINITY; l_run[rb] = 0.f; }
+    }
+    const int tb = f.tb;
+    rows_to_lds<FP8, false>(regs, s_tile, lane);
+    float ks[2] = {1.f, 1.f};
+    if constexpr (FP8) half_scales(kv, cs.g, f.pages, kv.k_scale, ks);
+    f = issue_next<FP8, false>(kv, cur, geo, lane, regs, unused);
+    f32x4 s[2][RB];
+    tile_qk<RB>(s_tile, qf, s, lane);
+    const bool edge = tb + kTileTokens > cs.L - n_q;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) s[sub][rb] *= c2 * ks[sub];
+      if (edge) {
+        const int r = 16 * rb + n;
+        const int last = cs.L - n_q + (r < R ? r / G : n_q - 1);
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (tb + 16 * sub + 4 * g4 + i > last) s[sub][rb][i] = -INFINITY;
+      }
+      const float mx = fmaxf(fmaxf(fmaxf(s[0][rb][0], s[0][rb][1]), fmaxf(s[0][rb][2], s[0][rb][3])),
+                             fmaxf(fmaxf(s[1][rb][0], s[1][rb][1]), fmaxf(s[1][rb][2], s[1][rb][3])));
+      const float m_new = fmaxf(m_run[rb], mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sum += fast_exp2(s[0][rb][i] - m_use) + fast_exp2(s[1][rb][i] - m_use);
+      l_run[rb] = l_run[rb] * fast_exp2(m_run[rb] - m_use) + sum;
+      m_run[rb] = m_new;
+    }
+  };
+  for (;;) {
+    if (!fa.valid) break;
+    tile(fa, ra);
+    if (!fb.valid) break;
+    tile(fb, rb_);
+  }
+  finish();
 }
 
 // ---------------------------------------------------------------- combine ---
@@ -357,117 +427,28 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_score_range(
   const LaneGeom<FP8> geo = lane_geom<FP8>(kv, lane);
   constexpr int kLoads = TileRegs<FP8>::kLoads;
   constexpr int kQIters = ((RB * 16 + 1) * 16 + kThreads - 1) / kThreads;
-  RangeWalk rw;
-  rw.total = ws.ctrl[0];
-  rw.w = blockIdx.x;
-  rw.unit = range_begin(rw.w, rw.total, ws.n_ranges);
-  rw.end = range_begin(rw.w + 1, rw.total, ws.n_ranges);
-  if (rw.unit >= rw.end) return;
-  Segment sg = first_segment(kv, ws, rw, lane);
-  do {
-    PageWin pw = open_window(kv, sg, lane);
-    const int nt = sg.tile1 - sg.tile0;
-    const int t_begin = sg.tile0 * kTileTokens;
-    u32x4 rk[kLoads], rv[kLoads];
-    int pgs[2], pgs_next[2];
-    issue_tile<FP8, true, true>(kv, sg, t_begin, pw, geo, lane, rk, rv, pgs);
-    {                                          // Q rows of the pair -> LDS (row R is the zero row of the padding)
-      u32x4 qtmp[kQIters];
-#pragma unroll
-      for (int j = 0; j < kQIters; ++j) {
-        const int ch = lane + kThreads * j;
-        const int r = ch >> 4, c = ch & 15;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (r < R) {
-          const int i = r / G, hg = r - i * G;
-          v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(sg.b) * n_q + i) * kv.num_q_heads + sg.g * G + hg) * kHeadDim + 8 * c);
-        }
-        qtmp[j] = v;
-      }
-#pragma unroll
-      for (int j = 0; j < kQIters; ++j) {
-        const int ch = lane + kThreads * j;
-        if (ch < (R + 1) * 16) *reinterpret_cast<u32x4*>(s_q + k_lds_addr(ch >> 4, ch & 15)) = qtmp[j];
-      }
-    }
-    float lse2[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) lse2[rb] = ws.lse2[static_cast<int64_t>(sg.pair) * (RB * 16) + 16 * rb + n];
-    float* sdst = scores + (static_cast<int64_t>(sg.b) * kv.num_kv_heads + sg.g) * score_stride;
-    f32x4 o[RB][8];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int d = 0; d < 8; ++d) o[rb][d] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int ti = 0; ti < nt; ++ti) {
-      const int tb = t_begin + ti * kTileTokens;
-      rows_to_lds<FP8, false>(rk, s_tile, lane);
-      // each register set goes back on the road as soon as its rows are in LDS
-      if (ti + 1 < nt) issue_tile<FP8, true, false>(kv, sg, tb + kTileTokens, pw, geo, lane, rk, rv, pgs_next);
-      float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
-      if constexpr (FP8) { half_scales(kv, sg.g, pgs, kv.k_scale, ks); half_scales(kv, sg.g, pgs, kv.v_scale, vs); }
-      f32x4 s[2][RB];
-      tile_qk_ldsq<RB>(s_tile, s_q, R, s, lane);
-      // the K rows are consumed: the V rows take their place
-      if (tb + kTileTokens > sg.L) zero_tail_rows<FP8>(rv, tb, sg.L, geo);
-      rows_to_lds<FP8, true>(rv, s_tile, lane);
-      if (ti + 1 < nt) {
-        int same[2];
-        issue_tile<FP8, false, true>(kv, sg, tb + kTileTokens, pw, geo, lane, rk, rv, same);
-        pgs[0] = pgs_next[0];
-        pgs[1] = pgs_next[1];
-      }
-      const bool edge = tb + kTileTokens > sg.L - n_q;
-      f32x4 tot[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-      bf16x8 p[RB];
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        f32x4 pr[2];
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-          const float sc = c2 * ks[sub];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) pr[sub][i] = fast_exp2(fmaf(s[sub][rb][i], sc, -lse2[rb]));
-        }
-        if (edge) {
-          const int r = 16 * rb + n;
-          const int last = sg.L - n_q + (r < R ? r / G : n_q - 1);
-#pragma unroll
-          for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (tb + 16 * sub + 4 * g4 + i > last) pr[sub][i] = 0.f;
-        }
-        tot[0] += pr[0];
-        tot[1] += pr[1];
-        if constexpr (FP8) { pr[0] *= vs[0]; pr[1] *= vs[1]; }
-        p[rb] = pack_p(pr[0], pr[1]);
-      }
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) tot[sub][i] = row16_sum(tot[sub][i]) * inv_r;
-        const int tok0 = tb + 16 * sub + 4 * g4;
-        if (n == 0) {
-          if (tok0 + 3 < sg.L) {
-            *reinterpret_cast<f32x4*>(sdst + tok0) = tot[sub];
-          } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (tok0 + i < sg.L) sdst[tok0 + i] = tot[sub][i];
-          }
-        }
-      }
-      tile_pv<RB>(s_tile, p, o, lane);
-    }
-    const bool whole = sg.tile0 == 0 && sg.tile1 == sg.tiles;
+#ifdef PILLAR_TRACING
+  const long long t_start = wall_clock64();
+#endif
+  for (int d = ((blockIdx.x >> 8) & 7) * (ws.debug >> 16); d > 0; --d) __builtin_amdgcn_s_sleep(127);   // experiment: staggered start
+  Cursor cur = open_cursor(kv, ws, lane);
+  if (!cur.live) return;
+  u32x4 rk[kLoads], rv[kLoads];
+  Flight f = issue_next<FP8, true>(kv, cur, geo, lane, rk, rv);
+  Segment cs = f.sg;
+  bool started = false;
+  float lse2[RB];
+  float* sdst = scores;
+  f32x4 o[RB][8];
+  auto finish = [&]() {                        // O of the segment: final when it is the whole pair, else a partial
+    const bool whole = cs.tile0 == 0 && cs.tile1 == cs.tiles;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       const int r = 16 * rb + n;
       if (r >= R) continue;
       if (whole) {
         const int i = r / G, hg = r - i * G;
-        uint16_t* dst = out + ((static_cast<int64_t>(sg.b) * n_q + i) * kv.num_q_heads + sg.g * G + hg) * kHeadDim;
+        uint16_t* dst = out + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim;
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
           u32x2 pk;
@@ -476,12 +457,104 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_score_range(
           *reinterpret_cast<u32x2*>(dst + 16 * db + 4 * g4) = pk;
         }
       } else {
-        float* dst = ws.part_o + (static_cast<int64_t>(sg.slot) * R + r) * kHeadDim + 4 * g4;
+        float* dst = ws.part_o + (static_cast<int64_t>(cs.slot) * R + r) * kHeadDim + 4 * g4;
 #pragma unroll
         for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + 16 * db) = o[rb][db];
       }
     }
-  } while (next_segment(kv, rw, sg));
+  };
+  while (f.valid) {
+    if (!started || f.sg.slot != cs.slot) {    // wave-uniform: the stream has entered another pair
+      if (started) finish();
+      cs = f.sg;
+      started = true;
+      {                                        // Q rows of the pair -> LDS (row R is the zero row of the padding)
+        u32x4 qtmp[kQIters];
+#pragma unroll
+        for (int j = 0; j < kQIters; ++j) {
+          const int ch = lane + kThreads * j;
+          const int r = ch >> 4, c = ch & 15;
+          u32x4 v = {0u, 0u, 0u, 0u};
+          if (r < R) {
+            const int i = r / G, hg = r - i * G;
+            v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim + 8 * c);
+          }
+          qtmp[j] = v;
+        }
+#pragma unroll
+        for (int j = 0; j < kQIters; ++j) {
+          const int ch = lane + kThreads * j;
+          if (ch < (R + 1) * 16) *reinterpret_cast<u32x4*>(s_q + k_lds_addr(ch >> 4, ch & 15)) = qtmp[j];
+        }
+      }
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) lse2[rb] = ws.lse2[static_cast<int64_t>(cs.pair) * (RB * 16) + 16 * rb + n];
+      sdst = scores + (static_cast<int64_t>(cs.b) * kv.num_kv_heads + cs.g) * score_stride;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int d = 0; d < 8; ++d) o[rb][d] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const int tb = f.tb;
+    rows_to_lds<FP8, false>(rk, s_tile, lane);
+    float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
+    if constexpr (FP8) { half_scales(kv, cs.g, f.pages, kv.k_scale, ks); half_scales(kv, cs.g, f.pages, kv.v_scale, vs); }
+    f32x4 s[2][RB];
+    tile_qk_ldsq<RB>(s_tile, s_q, R, s, lane);
+    // the K rows are consumed: the V rows take their place, and both register sets carry the next tile
+    if (tb + kTileTokens > cs.L) zero_tail_rows<FP8>(rv, tb, cs.L, geo);
+    rows_to_lds<FP8, true>(rv, s_tile, lane);
+    f = issue_next<FP8, true>(kv, cur, geo, lane, rk, rv);
+    const bool edge = tb + kTileTokens > cs.L - n_q;
+    f32x4 tot[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    bf16x8 p[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      f32x4 pr[2];
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        const float sc = c2 * ks[sub];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pr[sub][i] = fast_exp2(fmaf(s[sub][rb][i], sc, -lse2[rb]));
+      }
+      if (edge) {
+        const int r = 16 * rb + n;
+        const int last = cs.L - n_q + (r < R ? r / G : n_q - 1);
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (tb + 16 * sub + 4 * g4 + i > last) pr[sub][i] = 0.f;
+      }
+      tot[0] += pr[0];
+      tot[1] += pr[1];
+      if constexpr (FP8) { pr[0] *= vs[0]; pr[1] *= vs[1]; }
+      p[rb] = pack_p(pr[0], pr[1]);
+    }
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) tot[sub][i] = row16_sum(tot[sub][i]) * inv_r;
+      const int tok0 = tb + 16 * sub + 4 * g4;
+      if (n == 0) {
+        if (tok0 + 3 < cs.L) {
+          *reinterpret_cast<f32x4*>(sdst + tok0) = tot[sub];
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (tok0 + i < cs.L) sdst[tok0 + i] = tot[sub][i];
+        }
+      }
+    }
+    tile_pv<RB>(s_tile, p, o, lane);
+  }
+  finish();
+#ifdef PILLAR_TRACING
+  if ((blockIdx.x & 3) == 0 && blockIdx.x < 16384 && threadIdx.x == 0) {
+    ws.trace[(blockIdx.x >> 2) * 2] = t_start;
+    ws.trace[(blockIdx.x >> 2) * 2 + 1] = wall_clock64();
+  }
+#endif
 }
 
 // ---------------------------------------------------------------- merge -----
@@ -552,6 +625,7 @@ RangeWs carve(const KvView& kv, int n_q, void* workspace, size_t* total_bytes) {
   w.lse2 = reinterpret_cast<float*>(take(pairs * rpad * 4));
   w.rows_pad = static_cast<int32_t>(rpad);
   w.n_ranges = static_cast<int32_t>(n);
+  w.trace = reinterpret_cast<long long*>(take(8192 * 8));
   w.debug = options().debug;
   if (total_bytes) *total_bytes = off;
   return w;
@@ -595,6 +669,11 @@ bool verify_range_supported(const VerifyArgs& a) {
   // units are counted in 32 bits
   const int64_t units = static_cast<int64_t>(a.kv.batch) * a.kv.num_kv_heads * tiles_of_len(a.kv.max_seq_len);
   return units < (int64_t{1} << 30) && (a.score_stride % 4 == 0);
+}
+
+size_t verify_range_trace_offset(const KvView& kv, int n_q) {
+  const RangeWs w = carve(kv, n_q, reinterpret_cast<void*>(0x1000), nullptr);
+  return reinterpret_cast<uintptr_t>(w.trace) - 0x1000;
 }
 
 size_t verify_range_workspace(const KvView& kv, int n_q) {
