@@ -157,11 +157,11 @@ void pillar_profile_reset(void);
 int  pillar_profile_read(pillar_kernel_time* entries, int cap);
 
 /* Tuning knobs for benchmarking (process-wide, not thread-safe against
- * running calls).  Known names: "verify_chunk" (tokens per verification work
- * item, multiple of 128), "verify_grid" (persistent workgroups per compute
- * unit), "decode_wgs" (workgroup count the draft kernel aims for).  A value
- * of 0 restores the default.  Returns PILLAR_EINVAL for an unknown name or a
- * value outside the knob's range. */
+ * running calls).  Known names: "verify_waves" (wavefronts per compute unit
+ * that the two verification passes are divided among, 1..8) and "decode_rows"
+ * (rows of the index list per wavefront of the draft kernel, a multiple of 32
+ * up to 4096).  A value of 0 restores the default.  Returns PILLAR_EINVAL for
+ * an unknown name or a value outside the knob's range. */
 int pillar_set_option(const char* name, int64_t value);
 
 #ifdef __cplusplus

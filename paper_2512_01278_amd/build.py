@@ -20,7 +20,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 
 ARCH = "gfx950"
 # packed-fp32 instructions are switched off for all device code in this build
-DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"] + (["-DPILLAR_TRACING"] if os.environ.get("PILLAR_TRACING") else [])
+DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", f"--offload-arch={ARCH}", "-Wall", "-Wno-unused-function",
           "-Wno-unknown-warning-option", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

@@ -9,19 +9,21 @@
 // in flight as early as possible; the G query rows of the group ride along as
 // one 16-row MFMA block (the tile engine of mfma_tile.hpp with R = G).
 //
-// One workgroup per (request, KV head, split of the index list); its four
-// wavefronts take 32-row tiles round-robin.  Lists that fit one split are
-// finished in the kernel; longer lists leave (max, sum, O) partials that a
-// second small kernel combines.
+// One single-wavefront workgroup per (request, KV head, split of the index
+// list): a split is one or a few 32-row tiles, sized so that the grid is about
+// two rounds of what the chip holds at 16 wavefronts per compute unit.  With so
+// little work per wavefront the dependent chain index -> page id -> row is the
+// whole cost, and many independent wavefronts are what overlaps it.  Lists that
+// fit one split are finished in the kernel; longer lists leave (max, sum, O)
+// partials that a second small kernel combines.
 #include "launch.hpp"
 #include "mfma_tile.hpp"
 
 namespace pillar {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
-constexpr int kLdsBytes = kWaves * kWaveLds;
+constexpr int kThreads = 64;                   // one wavefront per workgroup
+constexpr int kMergeThreads = 256;
 
 struct DecWs {
   float* part_m;   // [B][Hkv][nsplit][16]  log2 domain
@@ -74,12 +76,12 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 }
 
 template <bool FP8>
-__global__ __launch_bounds__(kThreads, 2) void decode_split_mfma(DecodeArgs a, DecWs ws, int split_rows, int nsplit_max) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-  __shared__ float s_m[kWaves][16], s_l[kWaves][16];
+__global__ __launch_bounds__(kThreads, 3) void decode_split_mfma(DecodeArgs a, DecWs ws, int split_rows, int nsplit_max) {
+  // one tile buffer: the K rows, then (once S^T is done) the V rows of the same tile
+  __shared__ __attribute__((aligned(16))) uint8_t s_tile[kVTileBytes];
   const KvView& kv = a.kv;
   const int b = blockIdx.z, g = blockIdx.y, sp = blockIdx.x;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x;
   const int n = lane & 15, g4 = lane >> 4;
   const int G = kv.num_q_heads / kv.num_kv_heads;
   const int count = min(max(a.counts[b], 0), a.max_budget);
@@ -98,114 +100,85 @@ __global__ __launch_bounds__(kThreads, 2) void decode_split_mfma(DecodeArgs a, D
   const int nsplit = (count + split_rows - 1) / split_rows;
   const int ntiles = (j_end - j_begin + kTileTokens - 1) / kTileTokens;
   const int32_t* list = a.indices + (static_cast<int64_t>(b) * kv.num_kv_heads + g) * a.max_budget;
-  uint8_t* ktile = smem + wave * kWaveLds;
-  uint8_t* vtile = ktile + kKTileBytes;
   const float c2 = kv.sm_scale * kLog2e;
+
+  Gather cur = load_gather<FP8>(kv, list, b, g, j_begin, j_end, lane);
+  // B operand: lane (n, g4) holds Q[row n][32s + 8 g4 .. +7]
+  bf16x8 qf[1][4];
+  const uint16_t* qrow = static_cast<const uint16_t*>(a.q) + (static_cast<int64_t>(b) * kv.num_q_heads + g * G + n) * kHeadDim;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (n < G) v = *reinterpret_cast<const u32x4*>(qrow + 32 * s + 8 * g4);
+    qf[0][s] = as_bf16x8(v);
+  }
+  TileRegs<FP8> regs;
+  issue_gather<FP8>(kv, g, cur, regs, lane);
 
   f32x4 o[1][8];
 #pragma unroll
   for (int d = 0; d < 8; ++d) o[0][d] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;
-
-  if (wave < ntiles) {
-    // B operand: lane (n, g4) holds Q[row n][32s + 8 g4 .. +7]
-    bf16x8 qf[1][4];
-    const uint16_t* qrow = static_cast<const uint16_t*>(a.q) + (static_cast<int64_t>(b) * kv.num_q_heads + g * G + n) * kHeadDim;
+  for (int ti = 0; ti < ntiles; ++ti) {
+    const int jb = j_begin + ti * kTileTokens;
+    const bool more = ti + 1 < ntiles;
+    Gather nxt = cur;
+    if (more) nxt = load_gather<FP8>(kv, list, b, g, jb + kTileTokens, j_end, lane);
+    rows_to_lds<FP8, false>(regs.k, s_tile, lane);
+    f32x4 s[2][1];
+    tile_qk<1>(s_tile, qf, s, lane);
+    rows_to_lds<FP8, true>(regs.v, s_tile, lane);
+    if (more) issue_gather<FP8>(kv, g, nxt, regs, lane);
+    f32x4 vsc[2];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (n < G) v = *reinterpret_cast<const u32x4*>(qrow + 32 * s + 8 * g4);
-      qf[0][s] = as_bf16x8(v);
-    }
-    Gather cur = load_gather<FP8>(kv, list, b, g, j_begin + wave * kTileTokens, j_end, lane);
-    TileRegs<FP8> regs;
-    issue_gather<FP8>(kv, g, cur, regs, lane);
-    for (int ti = wave; ti < ntiles; ti += kWaves) {
-      const int jb = j_begin + ti * kTileTokens;
-      const bool more = ti + kWaves < ntiles;
-      Gather nxt = cur;
-      if (more) nxt = load_gather<FP8>(kv, list, b, g, jb + kWaves * kTileTokens, j_end, lane);
-      tile_to_lds<FP8>(regs, ktile, vtile, lane);
-      if (more) issue_gather<FP8>(kv, g, nxt, regs, lane);
-
-      f32x4 s[2][1];
-      tile_qk<1>(ktile, qf, s, lane);
-      f32x4 vsc[2];
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int slot = 16 * sub + 4 * g4 + i;
-          float sc = c2;
-          vsc[sub][i] = 1.f;
-          if constexpr (FP8) {
-            sc *= __shfl(cur.ks, slot, 64);
-            vsc[sub][i] = __shfl(cur.vs, slot, 64);
-          }
-          float v = s[sub][0][i] * sc;
-          if (jb + slot >= j_end) v = -INFINITY;
-          s[sub][0][i] = v;
-        }
-      }
-      float mx = fmaxf(fmaxf(fmaxf(s[0][0][0], s[0][0][1]), fmaxf(s[0][0][2], s[0][0][3])),
-                       fmaxf(fmaxf(s[1][0][0], s[1][0][1]), fmaxf(s[1][0][2], s[1][0][3])));
-      mx = fmaxf(mx, xor16(mx));
-      mx = fmaxf(mx, xor32(mx));
-      const float m_new = fmaxf(m_run, mx);              // finite: every tile has a valid row
-      const float alpha = exp2f(m_run - m_new);
-      f32x4 p0, p1;
-      float sum = 0.f;
+    for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        p0[i] = exp2f(s[0][0][i] - m_new);
-        p1[i] = exp2f(s[1][0][i] - m_new);
-        sum += p0[i] + p1[i];
+        const int slot = 16 * sub + 4 * g4 + i;
+        float sc = c2;
+        vsc[sub][i] = 1.f;
+        if constexpr (FP8) {
+          sc *= __shfl(cur.ks, slot, 64);
+          vsc[sub][i] = __shfl(cur.vs, slot, 64);
+        }
+        float v = s[sub][0][i] * sc;
+        if (jb + slot >= j_end) v = -INFINITY;
+        s[sub][0][i] = v;
       }
-      l_run = l_run * alpha + sum;
-      m_run = m_new;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(s[0][0][0], s[0][0][1]), fmaxf(s[0][0][2], s[0][0][3])),
+                     fmaxf(fmaxf(s[1][0][0], s[1][0][1]), fmaxf(s[1][0][2], s[1][0][3])));
+    mx = fmaxf(mx, xor16(mx));
+    mx = fmaxf(mx, xor32(mx));
+    const float m_new = fmaxf(m_run, mx);              // finite: every tile has a valid row
+    const float alpha = exp2f(m_run - m_new);
+    f32x4 p0, p1;
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      p0[i] = exp2f(s[0][0][i] - m_new);
+      p1[i] = exp2f(s[1][0][i] - m_new);
+      sum += p0[i] + p1[i];
+    }
+    l_run = l_run * alpha + sum;
+    m_run = m_new;
+    if (ti > 0) {
 #pragma unroll
       for (int d = 0; d < 8; ++d) o[0][d] *= alpha;
-      if constexpr (FP8) { p0 *= vsc[0]; p1 *= vsc[1]; }
-      bf16x8 p[1];
-      p[0] = pack_p(p0, p1);
-      tile_pv<1>(vtile, p, o, lane);
-      cur = nxt;
     }
-    l_run += xor16(l_run);
-    l_run += xor32(l_run);
+    if constexpr (FP8) { p0 *= vsc[0]; p1 *= vsc[1]; }
+    bf16x8 p[1];
+    p[0] = pack_p(p0, p1);
+    tile_pv<1>(s_tile, p, o, lane);
+    cur = nxt;
   }
+  l_run += xor16(l_run);
+  l_run += xor32(l_run);
 
-  // ---- combine the four wavefronts ----
-  if (g4 == 0) { s_m[wave][n] = m_run; s_l[wave][n] = l_run; }
-  __syncthreads();
-  float m_all = -INFINITY;
-#pragma unroll
-  for (int w = 0; w < kWaves; ++w) m_all = fmaxf(m_all, s_m[w][n]);
-  float l_all = 0.f;
-#pragma unroll
-  for (int w = 0; w < kWaves; ++w) l_all += s_l[w][n] * exp2f(s_m[w][n] - m_all);
-  const float mine = exp2f(m_run - m_all);
-#pragma unroll
-  for (int d = 0; d < 8; ++d) o[0][d] *= mine;
-  f32x4* xch = reinterpret_cast<f32x4*>(smem);
-#pragma unroll
-  for (int round = 0; round < 2; ++round) {
-    const int from = round == 0 ? 2 : 1, to = round == 0 ? 4 : 2;
-    __syncthreads();
-    if (wave >= from && wave < to) {
-#pragma unroll
-      for (int d = 0; d < 8; ++d) xch[(wave - from) * 512 + d * 64 + lane] = o[0][d];
-    }
-    __syncthreads();
-    if (wave < to - from && wave < from) {
-#pragma unroll
-      for (int d = 0; d < 8; ++d) o[0][d] += xch[wave * 512 + d * 64 + lane];
-    }
-  }
-  if (wave != 0 || n >= G) return;
+  if (n >= G) return;
   const int64_t row = static_cast<int64_t>(b) * kv.num_q_heads + g * G + n;
   if (nsplit == 1) {
-    const float inv = 1.0f / l_all;
+    const float inv = 1.0f / l_run;
     uint16_t* dst = out + row * kHeadDim;
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
@@ -214,17 +187,17 @@ __global__ __launch_bounds__(kThreads, 2) void decode_split_mfma(DecodeArgs a, D
       pk.y = pack_bf16x2(o[0][db][2] * inv, o[0][db][3] * inv);
       *reinterpret_cast<u32x2*>(dst + 16 * db + 4 * g4) = pk;
     }
-    if (a.lse && g4 == 0) a.lse[row] = (m_all + log2f(l_all)) * kLn2;
+    if (a.lse && g4 == 0) a.lse[row] = (m_run + log2f(l_run)) * kLn2;
   } else {
     const int64_t slot = (static_cast<int64_t>(b) * kv.num_kv_heads + g) * nsplit_max + sp;
-    if (g4 == 0) { ws.part_m[slot * 16 + n] = m_all; ws.part_l[slot * 16 + n] = l_all; }
+    if (g4 == 0) { ws.part_m[slot * 16 + n] = m_run; ws.part_l[slot * 16 + n] = l_run; }
     float* dst = ws.part_o + (slot * G + n) * kHeadDim;
 #pragma unroll
     for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + 16 * db + 4 * g4) = o[0][db];
   }
 }
 
-__global__ __launch_bounds__(kThreads) void decode_merge_mfma(DecodeArgs a, DecWs ws, int split_rows, int nsplit_max) {
+__global__ __launch_bounds__(kMergeThreads) void decode_merge_mfma(DecodeArgs a, DecWs ws, int split_rows, int nsplit_max) {
   const KvView& kv = a.kv;
   const int b = blockIdx.y, g = blockIdx.x;
   const int G = kv.num_q_heads / kv.num_kv_heads;
@@ -233,7 +206,7 @@ __global__ __launch_bounds__(kThreads) void decode_merge_mfma(DecodeArgs a, DecW
   if (nsplit <= 1) return;
   uint16_t* out = static_cast<uint16_t*>(a.out);
   const int64_t base = (static_cast<int64_t>(b) * kv.num_kv_heads + g) * nsplit_max;
-  for (int idx = threadIdx.x; idx < G * (kHeadDim / 4); idx += kThreads) {
+  for (int idx = threadIdx.x; idx < G * (kHeadDim / 4); idx += kMergeThreads) {
     const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
     float m = -INFINITY;
     for (int s = 0; s < nsplit; ++s) m = fmaxf(m, ws.part_m[(base + s) * 16 + r]);
@@ -254,16 +227,15 @@ __global__ __launch_bounds__(kThreads) void decode_merge_mfma(DecodeArgs a, DecW
   }
 }
 
-// rows of the index list per workgroup: enough workgroups to fill the chip,
-// few enough that the partials stay a small fraction of the gathered bytes
+// rows of the index list per wavefront: whole 32-row tiles, as few as keeps the grid within about
+// two rounds of the wavefronts the chip holds (16 per compute unit)
 int pick_split_rows(const KvView& kv, int max_budget) {
+  if (options().decode_rows > 0) return options().decode_rows;
   const int64_t pairs = static_cast<int64_t>(kv.batch) * kv.num_kv_heads;
-  const int64_t target_wgs = 1536;
-  int64_t rows = (pairs * max_budget + target_wgs - 1) / target_wgs;
-  rows = (rows + kTileTokens - 1) / kTileTokens * kTileTokens;
-  if (rows < 128) rows = 128;
-  if (rows > 1024) rows = 1024;
-  return static_cast<int>(rows);
+  const int64_t tiles = pairs * ((max_budget + kTileTokens - 1) / kTileTokens);
+  const int64_t target_waves = 8192;
+  const int64_t per_wave = (tiles + target_waves - 1) / target_waves;
+  return static_cast<int>(per_wave < 1 ? 1 : per_wave) * kTileTokens;
 }
 
 DecWs carve(const KvView& kv, int max_budget, void* workspace, size_t* total) {
@@ -284,25 +256,18 @@ DecWs carve(const KvView& kv, int max_budget, void* workspace, size_t* total) {
 
 template <bool FP8>
 hipError_t run(const DecodeArgs& a, hipStream_t st) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_split_mfma<FP8>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
   const KvView& kv = a.kv;
   const int split_rows = pick_split_rows(kv, a.max_budget);
   const int nsplit = (a.max_budget + split_rows - 1) / split_rows;
   const DecWs ws = carve(kv, a.max_budget, a.workspace, nullptr);
   {
     KernelTimer t("decode_split_mfma", st);
-    hipLaunchKernelGGL((decode_split_mfma<FP8>), dim3(nsplit, kv.num_kv_heads, kv.batch), dim3(kThreads), kLdsBytes, st,
-                       a, ws, split_rows, nsplit);
+    hipLaunchKernelGGL((decode_split_mfma<FP8>), dim3(nsplit, kv.num_kv_heads, kv.batch), dim3(kThreads), 0, st, a, ws, split_rows,
+                       nsplit);
   }
   if (nsplit > 1) {
     KernelTimer t("decode_merge_mfma", st);
-    hipLaunchKernelGGL(decode_merge_mfma, dim3(kv.num_kv_heads, kv.batch), dim3(kThreads), 0, st, a, ws, split_rows, nsplit);
+    hipLaunchKernelGGL(decode_merge_mfma, dim3(kv.num_kv_heads, kv.batch), dim3(kMergeThreads), 0, st, a, ws, split_rows, nsplit);
   }
   return hipGetLastError();
 }

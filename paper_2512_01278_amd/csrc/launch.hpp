@@ -64,13 +64,8 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
 bool verify_mfma_supported(const VerifyArgs& a);
 size_t verify_mfma_workspace(const KvView& kv, int n_q);
 hipError_t launch_verify_mfma(const VerifyArgs& a, hipStream_t s);
-bool verify_fused_supported(const VerifyArgs& a);      // needs a.scores
-size_t verify_fused_workspace(const KvView& kv, int n_q);
-size_t verify_fused_trace_offset(const KvView& kv, int n_q);
-hipError_t launch_verify_fused(const VerifyArgs& a, hipStream_t s);
 bool verify_range_supported(const VerifyArgs& a);      // needs a.scores
 size_t verify_range_workspace(const KvView& kv, int n_q);
-size_t verify_range_trace_offset(const KvView& kv, int n_q);
 hipError_t launch_verify_range(const VerifyArgs& a, hipStream_t s);
 bool decode_mfma_supported(const DecodeArgs& a);
 size_t decode_mfma_workspace(const KvView& kv, int max_budget);
@@ -81,11 +76,8 @@ bool force_generic();
 
 // process-wide tuning knobs (pillar_set_option); 0 = default
 struct Options {
-  int verify_chunk = 0;
-  int verify_grid = 0;
-  int verify_mode = 0;    // 0: two passes over equal ranges, 1: single persistent kernel, 2: two passes over fixed slices
-  int decode_wgs = 0;
-  int debug = 0;      // experiment switches, meaning private to the kernels
+  int verify_waves = 0;   // wavefronts per compute unit of the two verification passes
+  int decode_rows = 0;    // rows of the index list per wavefront of the draft kernel
 };
 Options& options();
 

@@ -123,8 +123,6 @@ size_t verify_workspace(const KvView& v, int n_q) {
   size_t b = 0;
   if (v.head_dim == 128 && v.page_size >= 16) {
     b = verify_mfma_workspace(v, n_q);
-    const size_t c = verify_fused_workspace(v, n_q);
-    if (c > b) b = c;
     const size_t d = verify_range_workspace(v, n_q);
     if (d > b) b = d;
   }
@@ -197,8 +195,7 @@ int pillar_verify_attn(const pillar_kv_t* kv, const void* q, int32_t spec_len_k,
   if (rc != PILLAR_OK) return rc;
   const hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
-  if (!force_generic() && options().verify_mode == 0 && verify_range_supported(a)) e = launch_verify_range(a, st);
-  else if (!force_generic() && verify_fused_supported(a)) e = launch_verify_fused(a, st);
+  if (!force_generic() && verify_range_supported(a)) e = launch_verify_range(a, st);
   else if (!force_generic() && verify_mfma_supported(a)) e = launch_verify_mfma(a, st);
   else e = launch_verify_generic(a, st);
   return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
@@ -259,32 +256,18 @@ int pillar_set_option(const char* name, int64_t value) {
   if (!name || value < 0) return PILLAR_EINVAL;
   Options& o = options();
   const std::string k(name);
-  if (k == "verify_chunk") {
-    if (value % 128 != 0 || value > 65536) return PILLAR_EINVAL;
-    o.verify_chunk = static_cast<int>(value);
-  } else if (k == "verify_grid") {
+  if (k == "verify_waves") {
     if (value > 8) return PILLAR_EINVAL;
-    o.verify_grid = static_cast<int>(value);
-  } else if (k == "verify_mode") {
-    if (value > 2) return PILLAR_EINVAL;
-    o.verify_mode = static_cast<int>(value);
-  } else if (k == "decode_wgs") {
-    if (value > (1 << 20)) return PILLAR_EINVAL;
-    o.decode_wgs = static_cast<int>(value);
-  } else if (k == "debug") {
-    o.debug = static_cast<int>(value);
+    o.verify_waves = static_cast<int>(value);
+  } else if (k == "decode_rows") {
+    if (value % 32 != 0 || value > 4096) return PILLAR_EINVAL;
+    o.decode_rows = static_cast<int>(value);
   } else {
     return PILLAR_EINVAL;
   }
   return PILLAR_OK;
 }
 
-// debugging aid (not part of the documented ABI): byte offset of the timestamp trace in the workspace
-size_t pillar_debug_trace_offset(const pillar_kv_t* kv, int32_t spec_len_k) {
-  if (check_kv(kv) != PILLAR_OK) return 0;
-  if (options().verify_mode == 0) return verify_range_trace_offset(make_view(kv), spec_len_k + 1);
-  return verify_fused_trace_offset(make_view(kv), spec_len_k + 1);
-}
 
 void pillar_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

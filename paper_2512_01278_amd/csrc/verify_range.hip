@@ -42,8 +42,6 @@ struct RangeWs {
   float* lse2;          // [pairs][rows_pad]      log2 domain
   int32_t rows_pad;     // 16 * row blocks
   int32_t n_ranges;     // N
-  int32_t debug;
-  long long* trace;     // [8192] timestamps (tracing builds only)
 };
 
 __host__ __device__ inline int tiles_of_len(int len) { return (len + kTileTokens - 1) / kTileTokens; }
@@ -427,10 +425,6 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_score_range(
   const LaneGeom<FP8> geo = lane_geom<FP8>(kv, lane);
   constexpr int kLoads = TileRegs<FP8>::kLoads;
   constexpr int kQIters = ((RB * 16 + 1) * 16 + kThreads - 1) / kThreads;
-#ifdef PILLAR_TRACING
-  const long long t_start = wall_clock64();
-#endif
-  for (int d = ((blockIdx.x >> 8) & 7) * (ws.debug >> 16); d > 0; --d) __builtin_amdgcn_s_sleep(127);   // experiment: staggered start
   Cursor cur = open_cursor(kv, ws, lane);
   if (!cur.live) return;
   u32x4 rk[kLoads], rv[kLoads];
@@ -549,12 +543,6 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_score_range(
     tile_pv<RB>(s_tile, p, o, lane);
   }
   finish();
-#ifdef PILLAR_TRACING
-  if ((blockIdx.x & 3) == 0 && blockIdx.x < 16384 && threadIdx.x == 0) {
-    ws.trace[(blockIdx.x >> 2) * 2] = t_start;
-    ws.trace[(blockIdx.x >> 2) * 2 + 1] = wall_clock64();
-  }
-#endif
 }
 
 // ---------------------------------------------------------------- merge -----
@@ -600,8 +588,8 @@ int num_cus() {
 // wavefronts of pass 2 a compute unit holds at once (registers: 2 per SIMD up to 32 rows, else 1; LDS allows as many)
 int ranges_for(int rb) {
   const int per_cu = rb >= 3 ? 4 : 8;
-  const int opt = options().verify_grid;
-  return (opt > 0 ? opt : per_cu) * num_cus();
+  const int opt = options().verify_waves;
+  return (opt > 0 && opt <= per_cu ? opt : per_cu) * num_cus();
 }
 
 int row_blocks(const KvView& kv, int n_q) { return (n_q * (kv.num_q_heads / kv.num_kv_heads) + 15) / 16; }
@@ -625,8 +613,6 @@ RangeWs carve(const KvView& kv, int n_q, void* workspace, size_t* total_bytes) {
   w.lse2 = reinterpret_cast<float*>(take(pairs * rpad * 4));
   w.rows_pad = static_cast<int32_t>(rpad);
   w.n_ranges = static_cast<int32_t>(n);
-  w.trace = reinterpret_cast<long long*>(take(8192 * 8));
-  w.debug = options().debug;
   if (total_bytes) *total_bytes = off;
   return w;
 }
@@ -669,11 +655,6 @@ bool verify_range_supported(const VerifyArgs& a) {
   // units are counted in 32 bits
   const int64_t units = static_cast<int64_t>(a.kv.batch) * a.kv.num_kv_heads * tiles_of_len(a.kv.max_seq_len);
   return units < (int64_t{1} << 30) && (a.score_stride % 4 == 0);
-}
-
-size_t verify_range_trace_offset(const KvView& kv, int n_q) {
-  const RangeWs w = carve(kv, n_q, reinterpret_cast<void*>(0x1000), nullptr);
-  return reinterpret_cast<uintptr_t>(w.trace) - 0x1000;
 }
 
 size_t verify_range_workspace(const KvView& kv, int n_q) {

@@ -50,6 +50,29 @@ def test_small_shapes(seed, kw):
     round_trip(small(seed, **kw))
 
 
+# ------------------------ work division of the two verification passes ----
+def test_many_tiny_requests_span_ranges():
+    """300 requests of 5..70 tokens: more requests than lanes in the wave-wide search for a range's
+    first request, ranges of a single tile, and (more ranges than tiles) empty ranges."""
+    rng = np.random.default_rng(7)
+    lens = rng.integers(5, 71, size=300).tolist()
+    w = small(110, B=300, Hq=8, Hkv=2, spec_k=4, seq_lens=lens, budgets=[8] * 300)
+    round_trip(w, what="300 tiny requests")
+
+
+def test_few_wide_ranges_cross_pairs_and_page_windows():
+    """One wavefront per compute unit: every range then covers several (request, head) pairs and
+    more than the 64 pages a lane register holds, so segments, partial slots and page windows change
+    inside a range."""
+    lens = [3000, 1100, 4097, 2500]
+    w = small(111, B=4, Hq=16, Hkv=4, spec_k=4, seq_lens=lens, budgets=[64] * 4)
+    pa.pillar_set_option("verify_waves", 1)
+    try:
+        round_trip(w, what="wide ranges")
+    finally:
+        pa.pillar_set_option("verify_waves", 0)
+
+
 # ------------------------------------------ the measured configs, reduced ----
 @pytest.mark.parametrize("cfg,batch", [(2, 2), (3, 4), (4, 1), (5, 2)])
 def test_config_reduced_batch(cfg, batch):
