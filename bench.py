@@ -60,6 +60,20 @@ def cpu_baseline(w, target_s: float = 12.0) -> dict:
             "sample_seconds": round(wall, 3)}
 
 
+def recorded_traffic(config: int):
+    """HBM bytes per step of the verification stage as rocprofv3's FETCH_SIZE / WRITE_SIZE counters gave
+    them (scaled by a copy kernel of known size) for this workload: a recorded figure, read from the
+    committed summary of those runs; None when there is none for the workload."""
+    path = os.path.join(ROOT, "profiles", f"bench_config{config}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("verify_stage_traffic_bytes:"):
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,6 +82,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--batch", type=int, default=None, help="truncate the batch (debugging only; marks the run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB -> 1 GiB float copy kernel (for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE readings; not timed, not part of any reported figure)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU only (the path shards by request or KV head with no "
@@ -123,6 +140,13 @@ def main() -> int:
     pa.pillar_profile_enable(False)
     prof = pa.pillar_profile_read()
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)                                          # one elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     ms_per_step = wall_ms / args.steps
     kern = {k: {"launches": n, "avg_us": round(ms * 1e3 / max(n, 1), 2)} for k, (n, ms) in prof.items()}
     stage_us = {"verify": 0.0, "topk": 0.0, "draft": 0.0}
@@ -166,7 +190,8 @@ def main() -> int:
         "algorithmic_bytes": {"verify": vb, "topk": tb, "draft": db},
         "kernels": kern,
         "roofline": {"bound": "hbm", "achieved": round(verify_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(verify_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(verify_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": None if args.batch is not None else recorded_traffic(args.config),
                      "kernel": "verification stage = " + " + ".join(sorted(k for k in prof if k.startswith("verify"))),
                      "avg_us": round(stage_us["verify"], 2), "algorithmic_bytes": vb,
                      "dominant_kernel": {"name": dom, "avg_us": round(dom_us, 2), "achieved": round(dom_gbps, 1),
@@ -175,7 +200,10 @@ def main() -> int:
                              "token and KV head + Q and O) over the SUM of the average durations of all its kernels "
                              "(HIP events on the launch stream): the method needs the log-sum-exp pass as much as the "
                              "score pass, so the stage, not its longest kernel, is priced against the roofline; "
-                             "dominant_kernel prices the same bytes against the longest kernel alone"},
+                             "dominant_kernel prices the same bytes against the longest kernel alone; traffic is not "
+                             "measured by this run: it is the HBM byte count (reads + writes, all kernels of the "
+                             "stage, one step) that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command "
+                             "recorded, see profiles/"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
