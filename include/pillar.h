@@ -158,9 +158,12 @@ int  pillar_profile_read(pillar_kernel_time* entries, int cap);
 
 /* Tuning knobs for benchmarking (process-wide, not thread-safe against
  * running calls).  Known names: "verify_waves" (wavefronts per compute unit
- * that the two verification passes are divided among, 1..8) and "decode_rows"
- * (rows of the index list per wavefront of the draft kernel, a multiple of 32
- * up to 4096).  A value of 0 restores the default.  Returns PILLAR_EINVAL for
+ * that the verification passes are divided among, 1..8), "verify_mode" (0: K
+ * is read once and the score statistic is rebuilt from 16-bit stashed
+ * exponentials, relative error up to 4.9e-4; 1: K is read twice and the
+ * statistic is computed from fp32 probabilities) and "decode_rows" (rows of
+ * the index list per wavefront of the draft kernel, a multiple of 32 up to
+ * 4096).  A value of 0 restores the default.  Returns PILLAR_EINVAL for
  * an unknown name or a value outside the knob's range. */
 int pillar_set_option(const char* name, int64_t value);
 

@@ -77,6 +77,7 @@ bool force_generic();
 // process-wide tuning knobs (pillar_set_option); 0 = default
 struct Options {
   int verify_waves = 0;   // wavefronts per compute unit of the two verification passes
+  int verify_mode = 0;    // 0: K read once, 16-bit exponentials stashed; 1: K read twice, fp32 probabilities
   int decode_rows = 0;    // rows of the index list per wavefront of the draft kernel
 };
 Options& options();

@@ -259,6 +259,9 @@ int pillar_set_option(const char* name, int64_t value) {
   if (k == "verify_waves") {
     if (value > 8) return PILLAR_EINVAL;
     o.verify_waves = static_cast<int>(value);
+  } else if (k == "verify_mode") {
+    if (value > 1) return PILLAR_EINVAL;
+    o.verify_mode = static_cast<int>(value);
   } else if (k == "decode_rows") {
     if (value % 32 != 0 || value > 4096) return PILLAR_EINVAL;
     o.decode_rows = static_cast<int>(value);

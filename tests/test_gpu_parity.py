@@ -73,6 +73,21 @@ def test_few_wide_ranges_cross_pairs_and_page_windows():
         pa.pillar_set_option("verify_waves", 0)
 
 
+def test_two_pass_variant_with_fp32_probabilities():
+    """verify_mode 1 reads K twice and never rounds a probability below fp32: same results, and the
+    score statistic then agrees with the oracle to fp32 accuracy."""
+    pa.pillar_set_option("verify_mode", 1)
+    try:
+        _, rep = round_trip(small(112, B=4, Hq=16, Hkv=4, spec_k=4, seq_lens=[3000, 40, 4097, 2500], budgets=[64] * 4),
+                            what="two-pass")
+        assert rep["scores"] < 5e-5
+        round_trip(small(113, kv_dtype="fp8_e4m3", Hq=16, Hkv=2, spec_k=4, seq_lens=[5, 255, 1000], budgets=[5, 16, 512]),
+                   what="two-pass fp8")
+        round_trip(gen.make_workload(4, batch=1), what="two-pass config4[:1]")
+    finally:
+        pa.pillar_set_option("verify_mode", 0)
+
+
 # ------------------------------------------ the measured configs, reduced ----
 @pytest.mark.parametrize("cfg,batch", [(2, 2), (3, 4), (4, 1), (5, 2)])
 def test_config_reduced_batch(cfg, batch):
