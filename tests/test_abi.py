@@ -106,6 +106,19 @@ def test_bad_call_arguments_are_rejected(lib):
     assert sd(cnt=None) == pb.PILLAR_EINVAL and sd(out=None) == pb.PILLAR_EINVAL and sd(mb=0) == pb.PILLAR_EINVAL
 
 
+def test_option_names_and_ranges(lib):
+    lib.pillar_set_option.restype = C.c_int
+    lib.pillar_set_option.argtypes = [C.c_char_p, C.c_int64]
+    ok = [(b"verify_waves", 4), (b"verify_waves", 0), (b"verify_mode", 1), (b"verify_mode", 0),
+          (b"decode_rows", 64), (b"decode_rows", 0)]
+    for name, value in ok:
+        assert lib.pillar_set_option(name, value) == 0, (name, value)
+    bad = [(b"verify_waves", 9), (b"verify_mode", 2), (b"decode_rows", 48), (b"decode_rows", 8192),
+           (b"verify_waves", -1), (b"no_such_knob", 1), (None, 1)]
+    for name, value in bad:
+        assert lib.pillar_set_option(name, value) == -1, (name, value)
+
+
 def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
     monkeypatch.setattr(pb, "_lib", None)
     monkeypatch.setattr(pb, "LIB_PATH", "/nonexistent/libpillar.so")
