@@ -61,10 +61,7 @@ hipError_t launch_decode_generic(const DecodeArgs& a, hipStream_t s);
 hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
 
 // matrix-core paths (bf16 queries, bf16 / fp8 KV, head_dim 128, pages >= 16)
-bool verify_mfma_supported(const VerifyArgs& a);
-size_t verify_mfma_workspace(const KvView& kv, int n_q);
-hipError_t launch_verify_mfma(const VerifyArgs& a, hipStream_t s);
-bool verify_range_supported(const VerifyArgs& a);      // needs a.scores
+bool verify_range_supported(const VerifyArgs& a);
 size_t verify_range_workspace(const KvView& kv, int n_q);
 hipError_t launch_verify_range(const VerifyArgs& a, hipStream_t s);
 bool decode_mfma_supported(const DecodeArgs& a);

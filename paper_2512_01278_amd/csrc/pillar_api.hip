@@ -122,9 +122,7 @@ size_t verify_workspace(const KvView& v, int n_q) {
   const size_t a = verify_generic_workspace(v, n_q);
   size_t b = 0;
   if (v.head_dim == 128 && v.page_size >= 16) {
-    b = verify_mfma_workspace(v, n_q);
-    const size_t d = verify_range_workspace(v, n_q);
-    if (d > b) b = d;
+    b = verify_range_workspace(v, n_q);
   }
   return a > b ? a : b;
 }
@@ -196,7 +194,6 @@ int pillar_verify_attn(const pillar_kv_t* kv, const void* q, int32_t spec_len_k,
   const hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
   if (!force_generic() && verify_range_supported(a)) e = launch_verify_range(a, st);
-  else if (!force_generic() && verify_mfma_supported(a)) e = launch_verify_mfma(a, st);
   else e = launch_verify_generic(a, st);
   return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
 }

@@ -607,7 +607,7 @@ __device__ __forceinline__ int stash_lane(int rb, int nblocks, int nv, int n, in
 // (half the bytes) where a wavefront has the SIMD to itself (3 and more row blocks).  Measured: depth 2
 // helps fp8 with 40 rows by 3 % and hurts bf16 with 36 rows by 4 %: those kernels are bound by their
 // own instruction stream, not by bytes in flight.
-template <int RB, bool FP8, int DEPTH>
+template <int RB, bool FP8, int DEPTH, bool STASH>
 __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_flash_range(KvView kv, const uint16_t* q, int n_q, RangeWs ws,
                                                                                  uint16_t* out) {
   __shared__ __attribute__((aligned(16))) uint8_t s_tile[kVTileBytes];
@@ -745,7 +745,7 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_flash_range(
         }
       l_run[rb] += sum;
       // the exponentials, 24 bits each, and the maximum they refer to
-      const int sl = stash_lane(rb, RB, nv, n, g4, lane);
+      const int sl = STASH ? stash_lane(rb, RB, nv, n, g4, lane) : -1;
       if (sl >= 0) {
         uint32_t c[8];
 #pragma unroll
@@ -757,7 +757,7 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_flash_range(
         packed.w = c[6] | (c[7] << 16);
         *reinterpret_cast<u32x4*>(st_base + sl * 16) = packed;
       }
-      if (g4 == 0) ws.m_ref[static_cast<int64_t>(unit) * (RB * 16) + 16 * rb + n] = m_use;
+      if (STASH && g4 == 0) ws.m_ref[static_cast<int64_t>(unit) * (RB * 16) + 16 * rb + n] = m_use;
       if constexpr (FP8) { pr[0] *= vs[0]; pr[1] *= vs[1]; }
       p[rb] = pack_p(pr[0], pr[1]);
     }
@@ -953,16 +953,20 @@ hipError_t run(const VerifyArgs& a, hipStream_t st) {
     KernelTimer t("verify_range_plan", st);
     hipLaunchKernelGGL(range_plan, dim3(1), dim3(1024), 0, st, kv, ws);
   }
-  if (options().verify_mode == 0) {
+  if (options().verify_mode == 0 || !a.scores) {
     {
       KernelTimer t("verify_flash_range", st);
-      hipLaunchKernelGGL((verify_flash_range<RB, FP8, (RB >= 3 && FP8 ? 2 : 1)>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
+      constexpr int kDepth = RB >= 3 && FP8 ? 2 : 1;
+      if (a.scores)
+        hipLaunchKernelGGL((verify_flash_range<RB, FP8, kDepth, true>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
+      else                                     // plain multi-query decode: nothing is stashed, nothing rebuilt
+        hipLaunchKernelGGL((verify_flash_range<RB, FP8, kDepth, false>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
     }
     {
       KernelTimer t("verify_lse_combine", st);
       hipLaunchKernelGGL(verify_lse_combine_range, dim3((pairs * ws.rows_pad + 255) / 256), dim3(256), 0, st, kv, a.n_q, ws, a.lse);
     }
-    {
+    if (a.scores) {
       KernelTimer t("verify_score_finalize", st);
       hipLaunchKernelGGL((verify_score_finalize<RB>), dim3(32 * num_cus()), dim3(kThreads), 0, st, kv, a.n_q, ws, a.scores,
                          a.score_stride);
@@ -996,10 +1000,21 @@ hipError_t run(const VerifyArgs& a, hipStream_t st) {
 }  // namespace
 
 bool verify_range_supported(const VerifyArgs& a) {
-  if (!a.scores || !verify_mfma_supported(a)) return false;
+  const KvView& kv = a.kv;
+  if (a.q_dtype != PILLAR_BF16) return false;
+  if (a.kv_dtype != PILLAR_BF16 && a.kv_dtype != PILLAR_FP8_E4M3) return false;
+  if (kv.head_dim != kHeadDim || kv.page_size < 16) return false;
+  if (row_blocks(kv, a.n_q) > 4) return false;
+  const int64_t align = a.kv_dtype == PILLAR_BF16 ? 8 : 16;      // elements per 16 bytes
+  if (kv.stride_page % align || kv.stride_head % align || kv.stride_slot % align) return false;
+  if ((reinterpret_cast<uintptr_t>(kv.k_pool) | reinterpret_cast<uintptr_t>(kv.v_pool) | reinterpret_cast<uintptr_t>(a.q) |
+       reinterpret_cast<uintptr_t>(a.out)) & 15u)
+    return false;
+  // the statistic is stored four tokens at a time
+  if (a.scores && ((reinterpret_cast<uintptr_t>(a.scores) & 15u) || (a.score_stride & 3))) return false;
   // units are counted in 32 bits
-  const int64_t units = static_cast<int64_t>(a.kv.batch) * a.kv.num_kv_heads * tiles_of_len(a.kv.max_seq_len);
-  return units < (int64_t{1} << 30) && (a.score_stride % 4 == 0);
+  const int64_t units = static_cast<int64_t>(kv.batch) * kv.num_kv_heads * tiles_of_len(kv.max_seq_len);
+  return units < (int64_t{1} << 30);
 }
 
 size_t verify_range_workspace(const KvView& kv, int n_q) {
