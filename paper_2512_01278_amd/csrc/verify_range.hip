@@ -594,8 +594,9 @@ __global__ __launch_bounds__(256) void verify_o_merge_range(KvView kv, int n_q, 
 // only the lanes of real rows (4 * nv, nv = R - 16 (RB - 1)); per lane 16 bytes = 8 values (tokens
 // 16 sub + 4 g4 + i, sub < 2, i < 4).
 __device__ __forceinline__ uint32_t stash_encode(float e) {
-  const uint32_t c = (__float_as_uint(e) + 0x1000u) >> 13;      // [8-bit exponent | 10-bit mantissa], rounded
-  return c > 0x10000u ? c - 0x10000u : 0u;                      // exponent rebased to 2^-63; below that: 0
+  // round at the 10th mantissa bit and rebase the exponent to 2^-63 in one addition; what falls below becomes 0
+  const int d = static_cast<int>(__float_as_uint(e)) + (0x1000 - 0x20000000);
+  return static_cast<uint32_t>(max(d, 0)) >> 13;                // [6-bit exponent | 10-bit mantissa]
 }
 __device__ __forceinline__ float stash_decode(uint32_t c) { return c ? __uint_as_float((c + 0x10000u) << 13) : 0.f; }
 
@@ -710,9 +711,8 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_flash_range(
     uint8_t* st_base = ws.stash + static_cast<int64_t>(unit) * tile_lanes * 16;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      f32x4 pr[2];
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub) pr[sub] = s[sub][rb] * (c2 * ks[sub]);
+      // logits stay unscaled until the exponential: the scales are positive, so the maximum commutes with them
+      f32x4 pr[2] = {s[0][rb], s[1][rb]};
       if (edge) {
         const int r = 16 * rb + n;
         const int last = cs.L - n_q + (r < R ? r / G : n_q - 1);
@@ -722,8 +722,9 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_flash_range(
           for (int i = 0; i < 4; ++i)
             if (tb + 16 * sub + 4 * g4 + i > last) pr[sub][i] = -INFINITY;
       }
-      float mx = fmaxf(fmaxf(fmaxf(pr[0][0], pr[0][1]), fmaxf(pr[0][2], pr[0][3])),
-                       fmaxf(fmaxf(pr[1][0], pr[1][1]), fmaxf(pr[1][2], pr[1][3])));
+      const float sc0 = c2 * ks[0], sc1 = c2 * ks[1];
+      float mx = fmaxf(fmaxf(fmaxf(pr[0][0], pr[0][1]), fmaxf(pr[0][2], pr[0][3])) * sc0,
+                       fmaxf(fmaxf(pr[1][0], pr[1][1]), fmaxf(pr[1][2], pr[1][3])) * sc1);
       mx = fmaxf(mx, xor16(mx));
       mx = fmaxf(mx, xor32(mx));                // the same in the four lanes of a row
       const float m_new = fmaxf(m_run[rb], mx);
@@ -740,7 +741,7 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_flash_range(
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          pr[sub][i] = fast_exp2(pr[sub][i] - m_use);
+          pr[sub][i] = fast_exp2(fmaf(pr[sub][i], sub == 0 ? sc0 : sc1, -m_use));
           sum += pr[sub][i];
         }
       l_run[rb] += sum;
@@ -1005,6 +1006,7 @@ bool verify_range_supported(const VerifyArgs& a) {
   if (a.kv_dtype != PILLAR_BF16 && a.kv_dtype != PILLAR_FP8_E4M3) return false;
   if (kv.head_dim != kHeadDim || kv.page_size < 16) return false;
   if (row_blocks(kv, a.n_q) > 4) return false;
+  if (!(kv.sm_scale > 0.f)) return false;       // the kernels take row maxima before scaling
   const int64_t align = a.kv_dtype == PILLAR_BF16 ? 8 : 16;      // elements per 16 bytes
   if (kv.stride_page % align || kv.stride_head % align || kv.stride_slot % align) return false;
   if ((reinterpret_cast<uintptr_t>(kv.k_pool) | reinterpret_cast<uintptr_t>(kv.v_pool) | reinterpret_cast<uintptr_t>(a.q) |
