@@ -148,8 +148,7 @@ __global__ __launch_bounds__(kThreads, 3) void decode_split_mfma(DecodeArgs a, D
     }
     float mx = fmaxf(fmaxf(fmaxf(s[0][0][0], s[0][0][1]), fmaxf(s[0][0][2], s[0][0][3])),
                      fmaxf(fmaxf(s[1][0][0], s[1][0][1]), fmaxf(s[1][0][2], s[1][0][3])));
-    mx = fmaxf(mx, xor16(mx));
-    mx = fmaxf(mx, xor32(mx));
+    mx = max_over_groups(mx);
     const float m_new = fmaxf(m_run, mx);              // finite: every tile has a valid row
     const float alpha = exp2f(m_run - m_new);
     f32x4 p0, p1;
@@ -172,8 +171,7 @@ __global__ __launch_bounds__(kThreads, 3) void decode_split_mfma(DecodeArgs a, D
     tile_pv<1>(s_tile, p, o, lane);
     cur = nxt;
   }
-  l_run += xor16(l_run);
-  l_run += xor32(l_run);
+  l_run = sum_over_groups(l_run);
 
   if (n >= G) return;
   const int64_t row = static_cast<int64_t>(b) * kv.num_q_heads + g * G + n;

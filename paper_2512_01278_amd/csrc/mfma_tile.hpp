@@ -55,6 +55,26 @@ __device__ __forceinline__ int v_lds_addr(int r, int c) { return r * kVRow + (c 
 __device__ __forceinline__ float xor16(float v) { return __shfl_xor(v, 16, 64); }
 __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
 
+// Maximum / sum over the four lanes l, l^16, l^32, l^48 (the four token groups of one query row),
+// left in all four.  v_permlane16_swap / v_permlane32_swap exchange 16- and 32-lane rows between two
+// registers on the vector ALU: with both operands holding v, one result holds each lane's own row
+// pair partner-first and the other own-first, so a commutative combine of the two results is the
+// pairwise combine -- no trip through the LDS crossbar as with a shuffle.
+__device__ __forceinline__ float max_over_groups(float v) {
+  typedef unsigned u2 __attribute__((ext_vector_type(2)));
+  u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+__device__ __forceinline__ float sum_over_groups(float v) {
+  typedef unsigned u2 __attribute__((ext_vector_type(2)));
+  u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(r.x) + __uint_as_float(r.y);
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+
 // sum over the 16 lanes of a DPP row (all 16 lanes receive the total)
 __device__ __forceinline__ float row16_sum(float v) {
   v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]

@@ -313,12 +313,10 @@ __global__ __launch_bounds__(kThreads, 2) void verify_lse_range(KvView kv, const
   auto finish = [&]() {                        // the 4 token groups of a row -> the segment's (m, l)
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      float mx = fmaxf(m_run[rb], xor16(m_run[rb]));
-      mx = fmaxf(mx, xor32(mx));
+      const float mx = max_over_groups(m_run[rb]);
       const float m_use = (mx == -INFINITY) ? 0.f : mx;
       float l = l_run[rb] * fast_exp2(m_run[rb] - m_use);
-      l += xor16(l);
-      l += xor32(l);
+      l = sum_over_groups(l);
       if (g4 == 0) {
         ws.part_m[static_cast<int64_t>(cs.slot) * (RB * 16) + 16 * rb + n] = mx;
         ws.part_l[static_cast<int64_t>(cs.slot) * (RB * 16) + 16 * rb + n] = l;
@@ -639,8 +637,7 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_flash_range(
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       float l = l_run[rb];
-      l += xor16(l);
-      l += xor32(l);
+      l = sum_over_groups(l);
       const int r = 16 * rb + n;
       if (g4 == 0) {
         ws.part_m[static_cast<int64_t>(cs.slot) * (RB * 16) + r] = m_run[rb];
@@ -725,8 +722,7 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_flash_range(
       const float sc0 = c2 * ks[0], sc1 = c2 * ks[1];
       float mx = fmaxf(fmaxf(fmaxf(pr[0][0], pr[0][1]), fmaxf(pr[0][2], pr[0][3])) * sc0,
                        fmaxf(fmaxf(pr[1][0], pr[1][1]), fmaxf(pr[1][2], pr[1][3])) * sc1);
-      mx = fmaxf(mx, xor16(mx));
-      mx = fmaxf(mx, xor32(mx));                // the same in the four lanes of a row
+      mx = max_over_groups(mx);                 // the same in the four lanes of a row
       const float m_new = fmaxf(m_run[rb], mx);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
       if (__any(m_new > m_run[rb])) {          // some row's maximum moved: rescale what is accumulated
