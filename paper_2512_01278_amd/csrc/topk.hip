@@ -132,6 +132,20 @@ __global__ __launch_bounds__(kThreads) void topk_radix(TopkArgs a) {
 }
 
 
+// Inclusive prefix sum over the 64 lanes of a wavefront on the vector ALU: shifts by 1, 2, 4, 8
+// inside each row of 16 lanes, then the last lane of row 0/2 is broadcast into row 1/3 and the last
+// lane of the lower half into the upper half (lanes shifted in from outside read 0).
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v) {
+  int x = static_cast<int>(v);
+  x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, false);   // row_shr:1
+  x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, false);   // row_shr:2
+  x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, false);   // row_shr:4
+  x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, false);   // row_shr:8
+  x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1 and 3
+  x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2 and 3
+  return static_cast<uint32_t>(x);
+}
+
 // Register-resident variant for rows of at most kThreads * KPT scores: every thread keeps KPT
 // consecutive keys, so the row is read once and the ordered emission is one scan.  The key is
 // resolved in three passes of 12, 12 and 8 bits: the wide first digit (sign, exponent and three
@@ -211,12 +225,7 @@ __global__ __launch_bounds__(kThreads) void topk_select(TopkArgs a) {
         c[0] = hist[255 - threadIdx.x];
         tot = c[0];
       }
-      uint32_t incl = tot;                   // inclusive scan over the workgroup
-#pragma unroll
-      for (int o = 1; o < kWave; o <<= 1) {
-        const uint32_t v = __shfl_up(incl, o, kWave);
-        if (lane >= o) incl += v;
-      }
+      uint32_t incl = wave_inclusive_sum(tot);   // inclusive scan over the workgroup: lanes, then wavefronts
       if (lane == kWave - 1) wave_sum[0][wave] = incl;
       __syncthreads();
       uint32_t before = 0;
@@ -255,12 +264,7 @@ __global__ __launch_bounds__(kThreads) void topk_select(TopkArgs a) {
     n_eq += (in && !take_all && key[j] == T) ? 1u : 0u;
   }
   // exclusive scans of both counts over the workgroup, in position order
-  uint32_t s_gt = n_gt, s_eq = n_eq;
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    const uint32_t v1 = __shfl_up(s_gt, o, kWave), v2 = __shfl_up(s_eq, o, kWave);
-    if (lane >= o) { s_gt += v1; s_eq += v2; }
-  }
+  uint32_t s_gt = wave_inclusive_sum(n_gt), s_eq = wave_inclusive_sum(n_eq);
   if (lane == kWave - 1) { wave_sum[0][wave] = s_gt; wave_sum[1][wave] = s_eq; }
   __syncthreads();
   uint32_t b_gt = 0, b_eq = 0;
