@@ -109,8 +109,10 @@ size_t pillar_workspace_bytes(const pillar_kv_t* kv, int32_t spec_len_k, int32_t
  *          softmax probability that row assigns to token t (0 where the
  *          causal mask hides t).  Entries t >= seq_lens[b] are not written.
  *          score_stride >= max_seq_len.  With bf16 queries the relative
- *          error of a score is at most 4.9e-4 in the default mode and that
- *          of fp32 arithmetic with "verify_mode" 1 (see pillar_set_option). */
+ *          error of a score is at most 4.9e-4 in the default mode (and a
+ *          probability more than 2^63 times smaller than the largest one its
+ *          row had met up to that token counts as 0), and that of fp32
+ *          arithmetic with "verify_mode" 1 (see pillar_set_option). */
 int pillar_verify_attn(const pillar_kv_t* kv, const void* q, int32_t spec_len_k,
                        void* out, float* lse, float* scores, int64_t score_stride,
                        void* workspace, size_t workspace_bytes, void* hip_stream);

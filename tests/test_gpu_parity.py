@@ -73,6 +73,16 @@ def test_few_wide_ranges_cross_pairs_and_page_windows():
         pa.pillar_set_option("verify_waves", 0)
 
 
+def test_peaked_attention_wide_logit_range():
+    """Sinks with ten times the key norm and strong pillars: row maxima jump by tens of bits between
+    tiles (rescaling of the running sums), and most tokens end with probabilities around 2^-40, far
+    down the exponent range of the 16-bit stash but inside it."""
+    w = small(114, B=2, Hq=16, Hkv=4, spec_k=4, seq_lens=[1500, 3100], budgets=[64, 128],
+              sink_tokens=4, sink_gain=10.0, pillar_gain=6.0)
+    _, rep = round_trip(w, what="peaked")
+    assert rep["scores"] < 1e-3
+
+
 def test_two_pass_variant_with_fp32_probabilities():
     """verify_mode 1 reads K twice and never rounds a probability below fp32: same results, and the
     score statistic then agrees with the oracle to fp32 accuracy."""
