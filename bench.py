@@ -81,6 +81,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--batch", type=int, default=None, help="truncate the batch (debugging only; marks the run)")
+    ap.add_argument("--three-calls", action="store_true",
+                    help="verify, Top-K and draft as three calls (the statistic goes through HBM between the first two) "
+                         "instead of pillar_verify_select + pillar_sparse_decode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB -> 1 GiB float copy kernel (for scaling rocprofv3's "
@@ -107,8 +110,11 @@ def main() -> int:
     stream = torch.cuda.current_stream()
 
     def step():
-        run.verify()
-        run.topk()
+        if args.three_calls:
+            run.verify()
+            run.topk()
+        else:
+            run.verify_select()
         run.decode()
 
     for _ in range(args.warmup):
@@ -177,6 +183,8 @@ def main() -> int:
         "dtype": {"f32": "f32", "bf16": "bf16", "fp8_e4m3": "bf16 (fp8 e4m3 KV)"}[w.kv_dtype],
         "data": "synthetic",
         "config": {"workload": f"config {args.config}: {gen.CONFIGS[args.config]}",
+                   "calls": "pillar_verify_attn + pillar_select_topk + pillar_sparse_decode" if args.three_calls
+                            else "pillar_verify_select + pillar_sparse_decode",
                    "batch": w.B, "context_tokens": int(w.seq_lens.sum()), "spec_len_k": w.spec_k,
                    "selected_rows": w.selected_rows(), "truncated": args.batch is not None},
         "tokens_per_s": round(q_tokens / (ms_per_step * 1e-3), 1),
@@ -194,13 +202,16 @@ def main() -> int:
                      "traffic": None if args.batch is not None else recorded_traffic(args.config),
                      "kernel": "verification stage = " + " + ".join(sorted(k for k in prof if k.startswith("verify"))),
                      "avg_us": round(stage_us["verify"], 2), "algorithmic_bytes": vb,
+                     "stage_includes_selection": not args.three_calls,
                      "dominant_kernel": {"name": dom, "avg_us": round(dom_us, 2), "achieved": round(dom_gbps, 1),
                                          "frac": round(dom_gbps / HBM_PEAK_GBPS, 4)},
                      "note": "algorithmic bytes of the verification stage (every KV row once + one fp32 score per "
                              "token and KV head + Q and O) over the SUM of the average durations of all its kernels "
                              "(HIP events on the launch stream): the method needs the log-sum-exp pass as much as the "
                              "score pass, so the stage, not its longest kernel, is priced against the roofline; "
-                             "dominant_kernel prices the same bytes against the longest kernel alone; traffic is not "
+                             "dominant_kernel prices the same bytes against the longest kernel alone; with "
+                             "pillar_verify_select the stage's time also contains the Top-K selection (its finish "
+                             "kernel selects from on-chip scores) while its bytes do not; traffic is not "
                              "measured by this run: it is the HBM byte count (reads + writes, all kernels of the "
                              "stage, one step) that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command "
                              "recorded, see profiles/"},

@@ -117,6 +117,18 @@ int pillar_verify_attn(const pillar_kv_t* kv, const void* q, int32_t spec_len_k,
                        void* out, float* lse, float* scores, int64_t score_stride,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* pillar_verify_attn and pillar_select_topk in one call: the critical tokens
+ * are selected from the score statistic while it is still on the chip, so it
+ * makes no round trip through memory between two launches.  Arguments as in
+ * the two calls; `scores` may be NULL when the caller does not want the
+ * statistic itself.  Results are identical to the two calls made in turn.
+ * The workspace needs pillar_workspace_bytes() bytes as for every call. */
+int pillar_verify_select(const pillar_kv_t* kv, const void* q, int32_t spec_len_k,
+                         void* out, float* lse, float* scores, int64_t score_stride,
+                         const int32_t* budgets, int32_t max_budget,
+                         int32_t* indices, int32_t* counts,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Critical-token selection (Section 4.1: Top-K on the averaged scores).
  *   scores   as written by pillar_verify_attn (all >= 0).
  *   budgets  device [B]: sparsity budget K of each request (>= 0).

@@ -20,6 +20,14 @@ struct KernelTimer {
   hipEvent_t start_ = nullptr;
 };
 
+// where a fused verification + selection leaves the critical tokens
+struct SelectOut {
+  const int32_t* budgets;
+  int32_t max_budget;
+  int32_t* indices;
+  int32_t* counts;
+};
+
 struct VerifyArgs {
   KvView kv;
   const void* q;
@@ -30,6 +38,7 @@ struct VerifyArgs {
   int32_t n_q;           // k+1
   int32_t q_dtype, kv_dtype;
   void* workspace;
+  const SelectOut* select = nullptr;   // non-null: also select the Top-K of every (request, KV head)
 };
 
 struct DecodeArgs {
@@ -64,6 +73,7 @@ hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
 bool verify_range_supported(const VerifyArgs& a);
 size_t verify_range_workspace(const KvView& kv, int n_q);
 hipError_t launch_verify_range(const VerifyArgs& a, hipStream_t s);
+bool verify_select_fused(const VerifyArgs& a);          // a.select can be served by the finish kernel itself
 bool decode_mfma_supported(const DecodeArgs& a);
 size_t decode_mfma_workspace(const KvView& kv, int max_budget);
 hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s);

@@ -145,6 +145,68 @@ bool force_generic() {
 
 using namespace pillar;
 
+namespace {
+
+// scores for an internal two-step fallback of pillar_verify_select live behind the stage workspaces
+size_t scratch_score_stride(const KvView& v) { return (static_cast<size_t>(v.max_seq_len) + 3) / 4 * 4; }
+size_t scratch_scores_bytes(const KvView& v) {
+  return static_cast<size_t>(v.batch) * v.num_kv_heads * scratch_score_stride(v) * sizeof(float);
+}
+
+int verify_common(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, void* out, float* lse, float* scores,
+                  int64_t score_stride, const SelectOut* select, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_kv(kv);
+  if (rc != PILLAR_OK) return rc;
+  rc = check_spec(kv, spec_len_k);
+  if (rc != PILLAR_OK) return rc;
+  if (!q || !out) return PILLAR_EINVAL;
+  if (scores && score_stride < kv->max_seq_len) return PILLAR_EINVAL;
+  VerifyArgs a;
+  a.kv = make_view(kv);
+  a.q = q;
+  a.out = out;
+  a.lse = lse;
+  a.scores = scores;
+  a.score_stride = score_stride;
+  a.n_q = spec_len_k + 1;
+  a.q_dtype = kv->q_dtype;
+  a.kv_dtype = kv->kv_dtype;
+  a.workspace = workspace;
+  a.select = select;
+  const size_t stage_ws = verify_workspace(a.kv, a.n_q);
+  rc = check_workspace(workspace, workspace_bytes, stage_ws + (select ? scratch_scores_bytes(a.kv) : 0));
+  if (rc != PILLAR_OK) return rc;
+  const hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (select && !(!force_generic() && verify_select_fused(a))) {
+    // two steps: the statistic goes through memory (the caller's buffer, or scratch behind the stage workspace)
+    a.select = nullptr;
+    if (!a.scores) {
+      a.scores = reinterpret_cast<float*>(static_cast<char*>(workspace) + align_up(stage_ws, 256));
+      a.score_stride = static_cast<int64_t>(scratch_score_stride(a.kv));
+    }
+    const hipError_t e1 = (!force_generic() && verify_range_supported(a)) ? launch_verify_range(a, st) : launch_verify_generic(a, st);
+    if (e1 != hipSuccess) return PILLAR_EHIP;
+    TopkArgs t;
+    t.scores = a.scores;
+    t.score_stride = a.score_stride;
+    t.seq_lens = a.kv.seq_lens;
+    t.budgets = select->budgets;
+    t.batch = a.kv.batch;
+    t.num_kv_heads = a.kv.num_kv_heads;
+    t.max_seq_len = a.kv.max_seq_len;
+    t.max_budget = select->max_budget;
+    t.indices = select->indices;
+    t.counts = select->counts;
+    return launch_topk(t, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+  }
+  hipError_t e;
+  if (!force_generic() && verify_range_supported(a)) e = launch_verify_range(a, st);
+  else e = launch_verify_generic(a, st);
+  return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+}
+
+}  // namespace
+
 extern "C" {
 
 int pillar_version(void) { return 100; }
@@ -164,6 +226,7 @@ size_t pillar_workspace_bytes(const pillar_kv_t* kv, int32_t spec_len_k, int32_t
   if (check_kv(kv) != PILLAR_OK || check_spec(kv, spec_len_k) != PILLAR_OK || max_budget < 0) return 0;
   const KvView v = make_view(kv);
   size_t need = verify_workspace(v, spec_len_k + 1);
+  need = align_up(need, 256) + scratch_scores_bytes(v);      // scratch for pillar_verify_select's two-step fallback
   const size_t dec = (v.head_dim == 128) ? decode_mfma_workspace(v, max_budget) : 0;
   if (dec > need) need = dec;
   return need < 256 ? 256 : need;
@@ -172,30 +235,20 @@ size_t pillar_workspace_bytes(const pillar_kv_t* kv, int32_t spec_len_k, int32_t
 int pillar_verify_attn(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, void* out, float* lse,
                        float* scores, int64_t score_stride, void* workspace, size_t workspace_bytes,
                        void* hip_stream) {
-  int rc = check_kv(kv);
-  if (rc != PILLAR_OK) return rc;
-  rc = check_spec(kv, spec_len_k);
-  if (rc != PILLAR_OK) return rc;
-  if (!q || !out) return PILLAR_EINVAL;
-  if (scores && score_stride < kv->max_seq_len) return PILLAR_EINVAL;
-  VerifyArgs a;
-  a.kv = make_view(kv);
-  a.q = q;
-  a.out = out;
-  a.lse = lse;
-  a.scores = scores;
-  a.score_stride = score_stride;
-  a.n_q = spec_len_k + 1;
-  a.q_dtype = kv->q_dtype;
-  a.kv_dtype = kv->kv_dtype;
-  a.workspace = workspace;
-  rc = check_workspace(workspace, workspace_bytes, verify_workspace(a.kv, a.n_q));
-  if (rc != PILLAR_OK) return rc;
-  const hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  hipError_t e;
-  if (!force_generic() && verify_range_supported(a)) e = launch_verify_range(a, st);
-  else e = launch_verify_generic(a, st);
-  return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+  return verify_common(kv, q, spec_len_k, out, lse, scores, score_stride, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+int pillar_verify_select(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, void* out, float* lse,
+                         float* scores, int64_t score_stride, const int32_t* budgets, int32_t max_budget,
+                         int32_t* indices, int32_t* counts, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  if (!budgets || !indices || !counts || max_budget < 1) return PILLAR_EINVAL;
+  SelectOut sel;
+  sel.budgets = budgets;
+  sel.max_budget = max_budget;
+  sel.indices = indices;
+  sel.counts = counts;
+  return verify_common(kv, q, spec_len_k, out, lse, scores, score_stride, &sel, workspace, workspace_bytes, hip_stream);
 }
 
 int pillar_select_topk(const float* scores, int64_t score_stride, const int32_t* seq_lens, const int32_t* budgets,

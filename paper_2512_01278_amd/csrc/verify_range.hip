@@ -25,6 +25,7 @@
 // segments have distinct sums because both indices grow along the layout).
 #include "launch.hpp"
 #include "mfma_tile.hpp"
+#include "topk_core.hpp"
 #include "verify_stream.hpp"
 
 namespace pillar {
@@ -892,6 +893,110 @@ __global__ __launch_bounds__(256) void verify_o_merge_flash(KvView kv, int n_q, 
   }
 }
 
+// ------------------------------------------------ finish with selection -----
+// Scores and Top-K in one kernel: one 1024-thread workgroup per (request, KV head) rebuilds the
+// pair's scores from the stash into LDS (tiles round-robin over its 16 wavefronts, two in flight
+// each), writes them out if the caller wants them, and selects straight from LDS -- the statistic
+// never makes the round trip through HBM between two launches (paper Section 4.1: identification
+// from the verification's own intermediates without extra memory traffic).
+template <int RB, int KPT>
+__global__ __launch_bounds__(kSelectThreads) void verify_select_finish(KvView kv, int n_q, RangeWs ws, float* scores,
+                                                                       int64_t score_stride, SelectOut sel) {
+  extern __shared__ __attribute__((aligned(16))) float s_scores[];      // kSelectThreads * KPT positions
+  __shared__ SelectLds lds;
+  const int pair = blockIdx.x;
+  const int b = pair / kv.num_kv_heads, g = pair - b * kv.num_kv_heads;
+  const int L = kv.seq_lens[b];
+  const int tiles = tiles_of_len(L);
+  const int u0 = ws.ureq[b] + g * tiles;
+  const int K = max(0, min(min(sel.budgets[b], L), sel.max_budget));
+  int32_t* out_idx = sel.indices + static_cast<int64_t>(pair) * sel.max_budget;
+  if (g == 0 && threadIdx.x == 0) sel.counts[b] = K;
+  for (int j = K + threadIdx.x; j < sel.max_budget; j += kSelectThreads) out_idx[j] = -1;
+  if (K == 0 && !scores) return;
+
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int n = lane & 15, g4 = lane >> 4;
+  const int G = kv.num_q_heads / kv.num_kv_heads;
+  const int R = n_q * G;
+  const int nv = R - 16 * (RB - 1);
+  const int tile_lanes = (RB - 1) * 64 + 4 * nv;
+  const float inv_r = 1.0f / static_cast<float>(R);
+  int sl[RB];
+  float lse2[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    sl[rb] = stash_lane(rb, RB, nv, n, g4, lane);
+    lse2[rb] = ws.lse2[static_cast<int64_t>(pair) * (RB * 16) + 16 * rb + n];
+  }
+  u32x4 st[2][RB];
+  float mref[2][RB];
+  auto fetch = [&](int tile, int buf) {
+    const int64_t u = u0 + tile;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      st[buf][rb] = u32x4{0u, 0u, 0u, 0u};
+      if (sl[rb] >= 0)
+        st[buf][rb] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ws.stash + (u * tile_lanes + sl[rb]) * 16));
+      mref[buf][rb] = ws.m_ref[u * (RB * 16) + 16 * rb + n];
+    }
+  };
+  auto tile_out = [&](int tile, int buf) {
+    f32x4 tot[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const float w = fast_exp2(mref[buf][rb] - lse2[rb]);     // rows beyond R: lse = +inf, w = 0
+      const uint32_t h[4] = {st[buf][rb].x, st[buf][rb].y, st[buf][rb].z, st[buf][rb].w};
+#pragma unroll
+      for (int k = 0; k < 8; ++k) tot[k >> 2][k & 3] += stash_decode((h[k >> 1] >> (16 * (k & 1))) & 0xffffu) * w;
+    }
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) tot[sub][i] = row16_sum(tot[sub][i]) * inv_r;
+      if (n == 0) *reinterpret_cast<f32x4*>(s_scores + tile * kTileTokens + 16 * sub + 4 * g4) = tot[sub];
+    }
+  };
+  {
+    int tile = wave;
+    if (tile < tiles) fetch(tile, 0);
+    while (tile < tiles) {
+      if (tile + kSelectWaves < tiles) fetch(tile + kSelectWaves, 1);
+      tile_out(tile, 0);
+      tile += kSelectWaves;
+      if (tile >= tiles) break;
+      if (tile + kSelectWaves < tiles) fetch(tile + kSelectWaves, 0);
+      tile_out(tile, 1);
+      tile += kSelectWaves;
+    }
+  }
+  __syncthreads();
+  if (scores) {
+    float* sdst = scores + static_cast<int64_t>(pair) * score_stride;
+    for (int t = 4 * threadIdx.x; t < L; t += 4 * kSelectThreads) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(s_scores + t);
+      if (t + 3 < L) {
+        *reinterpret_cast<f32x4*>(sdst + t) = v;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (t + i < L) sdst[t + i] = v[i];
+      }
+    }
+  }
+  if (K == 0) return;
+  const int t0 = threadIdx.x * KPT;
+  uint32_t key[KPT];
+#pragma unroll
+  for (int j = 0; j < KPT; j += 4) {
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (t0 + j < tiles * kTileTokens) v = *reinterpret_cast<const f32x4*>(s_scores + t0 + j);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) key[j + i] = order_key(v[i]);
+  }
+  select_topk_in_registers<KPT>(key, t0, L, K, out_idx, lds);
+}
+
 // ---------------------------------------------------------------- host ------
 int num_cus() {
   static int cus = 0;
@@ -950,11 +1055,11 @@ hipError_t run(const VerifyArgs& a, hipStream_t st) {
     KernelTimer t("verify_range_plan", st);
     hipLaunchKernelGGL(range_plan, dim3(1), dim3(1024), 0, st, kv, ws);
   }
-  if (options().verify_mode == 0 || !a.scores) {
+  if (options().verify_mode == 0 || !a.scores || a.select) {
     {
       KernelTimer t("verify_flash_range", st);
       constexpr int kDepth = RB >= 3 && FP8 ? 2 : 1;
-      if (a.scores)
+      if (a.scores || a.select)
         hipLaunchKernelGGL((verify_flash_range<RB, FP8, kDepth, true>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
       else                                     // plain multi-query decode: nothing is stashed, nothing rebuilt
         hipLaunchKernelGGL((verify_flash_range<RB, FP8, kDepth, false>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
@@ -963,7 +1068,27 @@ hipError_t run(const VerifyArgs& a, hipStream_t st) {
       KernelTimer t("verify_lse_combine", st);
       hipLaunchKernelGGL(verify_lse_combine_range, dim3((pairs * ws.rows_pad + 255) / 256), dim3(256), 0, st, kv, a.n_q, ws, a.lse);
     }
-    if (a.scores) {
+    if (a.select) {
+      KernelTimer t("verify_select_finish", st);
+      const SelectOut& sel = *a.select;
+#define PILLAR_SELECT(KPT)                                                                                                   \
+  {                                                                                                                          \
+    const size_t lds = static_cast<size_t>(kSelectThreads) * KPT * sizeof(float);                                           \
+    static bool attr_done = false;                                                                                           \
+    if (!attr_done) {                                                                                                        \
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_select_finish<RB, KPT>),               \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));          \
+      if (e != hipSuccess) return e;                                                                                         \
+      attr_done = true;                                                                                                      \
+    }                                                                                                                        \
+    hipLaunchKernelGGL((verify_select_finish<RB, KPT>), dim3(pairs), dim3(kSelectThreads), lds, st, kv, a.n_q, ws, a.scores, \
+                       a.score_stride, sel);                                                                                \
+  }
+      if (kv.max_seq_len <= kSelectThreads * 8) PILLAR_SELECT(8)
+      else if (kv.max_seq_len <= kSelectThreads * 16) PILLAR_SELECT(16)
+      else PILLAR_SELECT(32)
+#undef PILLAR_SELECT
+    } else if (a.scores) {
       KernelTimer t("verify_score_finalize", st);
       hipLaunchKernelGGL((verify_score_finalize<RB>), dim3(32 * num_cus()), dim3(kThreads), 0, st, kv, a.n_q, ws, a.scores,
                          a.score_stride);
@@ -1013,6 +1138,10 @@ bool verify_range_supported(const VerifyArgs& a) {
   // units are counted in 32 bits
   const int64_t units = static_cast<int64_t>(kv.batch) * kv.num_kv_heads * tiles_of_len(kv.max_seq_len);
   return units < (int64_t{1} << 30);
+}
+
+bool verify_select_fused(const VerifyArgs& a) {
+  return a.select && verify_range_supported(a) && options().verify_mode == 0 && a.kv.max_seq_len <= kSelectThreads * 32;
 }
 
 size_t verify_range_workspace(const KvView& kv, int n_q) {

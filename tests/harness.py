@@ -56,6 +56,11 @@ class GpuRun:
                               self.lse if with_lse else None, self.scores if with_scores else None,
                               self.workspace)
 
+    def verify_select(self, with_scores=True, with_lse=True):
+        pa.pillar_verify_select(self.dw.kv, self.dw.q, self.w.spec_k, self.out, self.lse if with_lse else None,
+                                self.scores if with_scores else None, self.dw.budgets, self.max_budget,
+                                self.indices, self.counts, self.workspace)
+
     def topk(self, scores=None):
         pa.pillar_select_topk(self.scores if scores is None else scores, self.dw.kv.seq_lens, self.dw.budgets,
                               self.w.max_seq_len, self.max_budget, self.indices, self.counts, self.workspace)
@@ -65,9 +70,12 @@ class GpuRun:
                                 self.counts if counts is None else counts, self.max_budget, self.d_out,
                                 self.d_lse, self.workspace)
 
-    def run_all(self):
-        self.verify()
-        self.topk()
+    def run_all(self, fused_select=False):
+        if fused_select:
+            self.verify_select()
+        else:
+            self.verify()
+            self.topk()
         self.decode()
         torch.cuda.synchronize()
 

@@ -125,6 +125,46 @@ def test_config_full_size_sampled(cfg):
     assert not torch.isnan(run.out.float()).any() and not torch.isnan(run.d_out.float()).any()
 
 
+# --------------------------- verification and selection in one call ----------
+def _same_as_two_calls(w, what, with_scores=True):
+    """pillar_verify_select against pillar_verify_attn + pillar_select_topk on the same inputs: every
+    output bit for bit, and the whole round against the oracle."""
+    two = GpuRun(w)
+    two.run_all()
+    one = GpuRun(w)
+    one.verify_select(with_scores=with_scores)
+    one.decode()
+    torch.cuda.synchronize()
+    assert torch.equal(one.out.view(torch.int16), two.out.view(torch.int16)), f"{what}: out differs"
+    assert torch.equal(one.lse, two.lse), f"{what}: lse differs"
+    assert torch.equal(one.counts, two.counts) and torch.equal(one.indices, two.indices), f"{what}: selection differs"
+    assert torch.equal(one.d_out.view(torch.int16), two.d_out.view(torch.int16)), f"{what}: draft differs"
+    if with_scores:
+        for b in range(w.B):
+            L = int(w.seq_lens[b])
+            assert torch.equal(one.scores[b, :, :L], two.scores[b, :, :L]), f"{what}: scores differ, request {b}"
+        rep = compare_with_oracle(w, one, None, what)
+        print(f"[ok] {what}: {rep}", flush=True)
+
+
+def test_verify_select_equals_the_two_calls():
+    _same_as_two_calls(small(120, B=4, Hq=16, Hkv=4, spec_k=4, seq_lens=[5, 700, 2049, 33], budgets=[8, 64, 128, 40]), "fused select")
+    _same_as_two_calls(small(121, kv_dtype="fp8_e4m3", Hq=16, Hkv=2, spec_k=4, seq_lens=[5, 255, 1000], budgets=[5, 16, 512]),
+                       "fused select fp8")
+    _same_as_two_calls(small(122, P=64, spec_k=8, Hq=8, Hkv=2, seq_lens=[9, 64, 700], budgets=[9, 64, 100]), "fused select 36 rows")
+    _same_as_two_calls(small(123, B=2, Hq=8, Hkv=2, spec_k=2, seq_lens=[9000, 300], budgets=[300, 300]), "fused select, 16 keys per thread")
+    _same_as_two_calls(small(124, B=3, Hq=8, Hkv=2, spec_k=2, seq_lens=[3, 130, 517], budgets=[2, 40, 64]), "fused select, no scores",
+                       with_scores=False)
+    # shapes the matrix-core path does not take go through the two calls inside the library
+    _same_as_two_calls(small(125, q_dtype="f32", kv_dtype="f32", D=64), "fused select, generic path")
+    _same_as_two_calls(small(126, q_dtype="f32", kv_dtype="f32", D=64), "fused select, generic path, no scores", with_scores=False)
+
+
+def test_verify_select_reduced_configs():
+    for cfg, batch in [(3, 4), (5, 2)]:
+        _same_as_two_calls(gen.make_workload(cfg, batch=batch), f"fused select config{cfg}[:{batch}]")
+
+
 # ----------------------------------------------------------- edge cases ------
 def test_outputs_are_bit_identical_from_run_to_run():
     w = small(201, seq_lens=[40, 300, 1500], budgets=[8, 30, 100])
