@@ -100,6 +100,12 @@ def test_bad_call_arguments_are_rejected(lib):
     assert tk(scores=None) == pb.PILLAR_EINVAL and tk(budgets=None) == pb.PILLAR_EINVAL
     assert tk(counts=None) == pb.PILLAR_EINVAL and tk(batch=0) == pb.PILLAR_EINVAL
     assert tk(mb=0) == pb.PILLAR_EINVAL and tk(stride=512) == pb.PILLAR_EINVAL
+    vs = lambda **k: lib.pillar_verify_select(C.byref(s), k.get("q", FAKE), 4, FAKE, None, None, 0, k.get("budgets", FAKE),
+                                              k.get("mb", 256), k.get("idx", FAKE), k.get("cnt", FAKE), k.get("ws", FAKE),
+                                              k.get("wsz", 1 << 40), None)
+    assert vs(q=None) == pb.PILLAR_EINVAL and vs(budgets=None) == pb.PILLAR_EINVAL and vs(idx=None) == pb.PILLAR_EINVAL
+    assert vs(cnt=None) == pb.PILLAR_EINVAL and vs(mb=0) == pb.PILLAR_EINVAL
+    assert vs(ws=None) == pb.PILLAR_EWORKSPACE and vs(wsz=128) == pb.PILLAR_EWORKSPACE
     sd = lambda **k: lib.pillar_sparse_decode(C.byref(s), k.get("q", FAKE), k.get("idx", FAKE), k.get("cnt", FAKE),
                                               k.get("mb", 256), k.get("out", FAKE), None, FAKE, 1 << 40, None)
     assert sd(q=None) == pb.PILLAR_EINVAL and sd(idx=None) == pb.PILLAR_EINVAL
