@@ -91,7 +91,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU only (the path shards by request or KV head with no "
-              "exchange; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "exchange, so a second GPU would only run a second copy). Run with --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np
