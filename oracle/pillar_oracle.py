@@ -194,3 +194,45 @@ def run_all(w):
     d_out, d_lse = sparse_decode(w, idx, counts)
     return dict(out=out, lse=lse, scores=scores, indices=idx, counts=counts,
                 draft_out=d_out, draft_lse=d_lse)
+
+
+# ---------------------------------------------------------------------------
+def window_indices(seq_lens, budgets, num_kv_heads, sink_tokens, max_budget=None):
+    """Static 'attention sinks + recent window' selection: the sliding-window
+    draft that the paper's related work and baselines use in place of a
+    dynamic pattern (Section 2, "Sparse self-speculation"; baselines of
+    Section 5).  Per request K' = min(budget, L, max_budget); the list holds
+    the first min(sink_tokens, K') positions and the last K' minus that many,
+    ascending, the same for every KV head, padded with -1; counts = K'.
+    """
+    seq_lens = np.asarray(seq_lens)
+    B = len(seq_lens)
+    if max_budget is None:
+        max_budget = int(np.max(budgets)) if B else 0
+    idx = np.full((B, num_kv_heads, max_budget), -1, dtype=np.int32)
+    counts = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        L = int(seq_lens[b])
+        kk = min(int(budgets[b]), L, max_budget)
+        ns = min(int(sink_tokens), kk)
+        positions = list(range(ns)) + list(range(L - (kk - ns), L))
+        counts[b] = kk
+        idx[b, :, :kk] = np.asarray(positions, dtype=np.int32)[None, :]
+    return idx, counts
+
+
+def extend_indices(indices, counts, first_new, n_new):
+    """Tokens generated after the last verification have no score yet; a draft
+    step must still see them (a reading: the paper is silent).  Appends the
+    positions first_new[b] .. first_new[b] + n_new[b] - 1 to every head's list
+    of request b, as many as still fit, and returns the new lists and counts.
+    """
+    idx = np.array(indices, dtype=np.int32, copy=True)
+    cnt = np.array(counts, dtype=np.int32, copy=True)
+    cap = idx.shape[2]
+    for b in range(idx.shape[0]):
+        c = int(cnt[b])
+        n = max(0, min(int(n_new[b]), cap - c))
+        idx[b, :, c:c + n] = (int(first_new[b]) + np.arange(n, dtype=np.int32))[None, :]
+        cnt[b] = c + n
+    return idx, cnt

@@ -286,3 +286,36 @@ def test_bf16_roundtrip_against_library():
     want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(bits, want)
     assert np.array_equal(oracle.decode_tensor(bits, "bf16"), torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy())
+
+
+# ---------------------------------------------------------------- index lists
+def test_window_list_is_topk_of_a_sink_plus_recency_score():
+    """'Sinks + recent window' is the Top-K of a score that puts the sinks first and then grows with
+    the position: checked against the (separately pinned) Top-K routine, and against hand-written lists."""
+    seq_lens = np.array([5, 40, 17, 3], dtype=np.int32)
+    budgets = np.array([8, 12, 17, 2], dtype=np.int32)
+    sink = 4
+    idx, cnt = oracle.window_indices(seq_lens, budgets, 3, sink, max_budget=16)
+    scores = np.zeros((4, 3, 40))
+    for b, L in enumerate(seq_lens):
+        scores[b, :, :L] = (np.arange(L) + 1.0) / (L + 1.0)
+        scores[b, :, :min(sink, L)] = 2.0 + np.arange(min(sink, L))[::-1]     # sink 0 highest
+    ref_idx, ref_cnt = oracle.select_topk(scores, seq_lens, budgets, max_budget=16)
+    assert np.array_equal(cnt, ref_cnt) and np.array_equal(idx, ref_idx)
+    assert cnt.tolist() == [5, 12, 16, 2]
+    assert idx[1, 0, :12].tolist() == [0, 1, 2, 3, 32, 33, 34, 35, 36, 37, 38, 39]
+    assert idx[3, 2, :2].tolist() == [0, 1] and idx[3, 2, 2] == -1          # budget below the sink count: sinks only
+    assert idx[0, 1, :5].tolist() == [0, 1, 2, 3, 4]                        # budget above the length: everything
+
+
+def test_extend_indices_by_hand():
+    idx = np.full((2, 2, 6), -1, dtype=np.int32)
+    idx[0, :, :3] = [1, 4, 7]
+    idx[1, :, :5] = [0, 1, 2, 3, 9]
+    cnt = np.array([3, 5], dtype=np.int32)
+    new_idx, new_cnt = oracle.extend_indices(idx, cnt, first_new=[10, 20], n_new=[2, 3])
+    assert new_cnt.tolist() == [5, 6]                                        # the second list has room for one only
+    assert new_idx[0, 1].tolist() == [1, 4, 7, 10, 11, -1]
+    assert new_idx[1, 0].tolist() == [0, 1, 2, 3, 9, 20]
+    assert idx[0, 0, 3] == -1                                                # inputs untouched
+
