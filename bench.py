@@ -84,6 +84,9 @@ def main() -> int:
     ap.add_argument("--three-calls", action="store_true",
                     help="verify, Top-K and draft as three calls (the statistic goes through HBM between the first two) "
                          "instead of pillar_verify_select + pillar_sparse_decode")
+    ap.add_argument("--index-source", choices=["pillar", "window"], default="pillar",
+                    help="window: the sliding-window draft the paper compares against -- verification without the "
+                         "statistic, a static list of 4 sinks + the most recent tokens with the same budgets, draft")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB -> 1 GiB float copy kernel (for scaling rocprofv3's "
@@ -110,7 +113,10 @@ def main() -> int:
     stream = torch.cuda.current_stream()
 
     def step():
-        if args.three_calls:
+        if args.index_source == "window":
+            run.verify(with_scores=False)
+            pa.pillar_window_indices(run.dw.kv.seq_lens, run.dw.budgets, w.Hkv, 4, run.max_budget, run.indices, run.counts)
+        elif args.three_calls:
             run.verify()
             run.topk()
         else:
@@ -158,7 +164,7 @@ def main() -> int:
     stage_us = {"verify": 0.0, "topk": 0.0, "draft": 0.0}
     for k, (n, ms) in prof.items():
         per_step = ms * 1e3 / args.steps
-        stage = "verify" if k.startswith("verify") else "topk" if k.startswith("topk") else "draft"
+        stage = "verify" if k.startswith("verify") else "topk" if k.startswith(("topk", "window")) else "draft"
         stage_us[stage] += per_step
     vb, db, tb = w.verify_bytes(), w.draft_bytes(), w.topk_bytes()
     verify_gbps = vb / (stage_us["verify"] * 1e-6) / 1e9 if stage_us["verify"] else 0.0
@@ -183,7 +189,10 @@ def main() -> int:
         "dtype": {"f32": "f32", "bf16": "bf16", "fp8_e4m3": "bf16 (fp8 e4m3 KV)"}[w.kv_dtype],
         "data": "synthetic",
         "config": {"workload": f"config {args.config}: {gen.CONFIGS[args.config]}",
-                   "calls": "pillar_verify_attn + pillar_select_topk + pillar_sparse_decode" if args.three_calls
+                   "index_source": args.index_source,
+                   "calls": "pillar_verify_attn (no statistic) + pillar_window_indices + pillar_sparse_decode"
+                            if args.index_source == "window" else
+                            "pillar_verify_attn + pillar_select_topk + pillar_sparse_decode" if args.three_calls
                             else "pillar_verify_select + pillar_sparse_decode",
                    "batch": w.B, "context_tokens": int(w.seq_lens.sum()), "spec_len_k": w.spec_k,
                    "selected_rows": w.selected_rows(), "truncated": args.batch is not None},
@@ -216,7 +225,7 @@ def main() -> int:
                              "stage, one step) that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command "
                              "recorded, see profiles/"},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.index_source == "pillar":
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out, ensure_ascii=False))
     return 0

@@ -157,6 +157,27 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
                          const int32_t* counts, int32_t max_budget, void* out, float* lse,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Index lists from other sources for pillar_sparse_decode (Section 4.2: at
+ * page size 1 any token set is a list).
+ *
+ * pillar_window_indices: the static "attention sinks + recent window" pattern
+ * of the sliding-window drafts the paper compares against (Section 2).  For
+ * request b, K' = min(budgets[b], seq_lens[b], max_budget); every head's list
+ * holds the first min(sink_tokens, K') positions and the last K' minus that
+ * many, ascending, padded with -1; counts[b] = K'.  All arrays on the device,
+ * layouts as in pillar_select_topk.
+ *
+ * pillar_extend_indices: tokens generated since the last verification have no
+ * score yet but must be visible to a draft step: appends the positions
+ * first_new[b] .. first_new[b]+n_new[b]-1 to every head's list of request b
+ * (as many as fit below max_budget) and adds that number to counts[b]. */
+int pillar_window_indices(const int32_t* seq_lens, const int32_t* budgets, int32_t batch,
+                          int32_t num_kv_heads, int32_t sink_tokens, int32_t max_budget,
+                          int32_t* indices, int32_t* counts, void* hip_stream);
+int pillar_extend_indices(int32_t* indices, int32_t* counts, const int32_t* first_new,
+                          const int32_t* n_new, int32_t batch, int32_t num_kv_heads,
+                          int32_t max_budget, void* hip_stream);
+
 /* Per-kernel timing for benchmarks.  pillar_profile_enable(1) makes every
  * later launch of this library be bracketed by HIP events on its stream;
  * pillar_profile_read synchronises the device, then fills up to `cap` entries

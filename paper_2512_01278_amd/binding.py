@@ -22,7 +22,8 @@ PILLAR_F32, PILLAR_BF16, PILLAR_FP8_E4M3 = 0, 1, 2
 DTYPE_CODE = {"f32": PILLAR_F32, "bf16": PILLAR_BF16, "fp8_e4m3": PILLAR_FP8_E4M3}
 
 EXPORTS = ("pillar_version", "pillar_status_string", "pillar_workspace_bytes", "pillar_verify_attn",
-           "pillar_verify_select", "pillar_select_topk", "pillar_sparse_decode", "pillar_profile_enable", "pillar_profile_reset",
+           "pillar_verify_select", "pillar_select_topk", "pillar_sparse_decode", "pillar_window_indices",
+           "pillar_extend_indices", "pillar_profile_enable", "pillar_profile_reset",
            "pillar_profile_read", "pillar_set_option")
 
 
@@ -81,6 +82,12 @@ def load() -> C.CDLL:
     lib.pillar_sparse_decode.restype = C.c_int
     lib.pillar_sparse_decode.argtypes = [C.POINTER(pillar_kv_t), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.pillar_window_indices.restype = C.c_int
+    lib.pillar_window_indices.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]
+    lib.pillar_extend_indices.restype = C.c_int
+    lib.pillar_extend_indices.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                          C.c_void_p]
     lib.pillar_set_option.restype = C.c_int
     lib.pillar_set_option.argtypes = [C.c_char_p, C.c_int64]
     lib.pillar_profile_enable.restype = None
@@ -203,6 +210,20 @@ def pillar_sparse_decode(kv: KvCache, q: torch.Tensor, indices: torch.Tensor, co
     rc = load().pillar_sparse_decode(C.byref(s), q.data_ptr(), indices.data_ptr(), counts.data_ptr(), max_budget,
                                      out.data_ptr(), _ptr(lse), _ptr(workspace), wsz, _stream(stream))
     _check(rc, "pillar_sparse_decode")
+
+
+def pillar_window_indices(seq_lens: torch.Tensor, budgets: torch.Tensor, num_kv_heads: int, sink_tokens: int,
+                          max_budget: int, indices: torch.Tensor, counts: torch.Tensor, stream=None) -> None:
+    rc = load().pillar_window_indices(seq_lens.data_ptr(), budgets.data_ptr(), seq_lens.shape[0], num_kv_heads, sink_tokens,
+                                      max_budget, indices.data_ptr(), counts.data_ptr(), _stream(stream))
+    _check(rc, "pillar_window_indices")
+
+
+def pillar_extend_indices(indices: torch.Tensor, counts: torch.Tensor, first_new: torch.Tensor, n_new: torch.Tensor,
+                          stream=None) -> None:
+    rc = load().pillar_extend_indices(indices.data_ptr(), counts.data_ptr(), first_new.data_ptr(), n_new.data_ptr(),
+                                      indices.shape[0], indices.shape[1], indices.shape[2], _stream(stream))
+    _check(rc, "pillar_extend_indices")
 
 
 def pillar_set_option(name: str, value: int) -> None:

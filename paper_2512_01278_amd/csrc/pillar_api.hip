@@ -302,6 +302,22 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
   return launch_decode_generic(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
 }
 
+int pillar_window_indices(const int32_t* seq_lens, const int32_t* budgets, int32_t batch, int32_t num_kv_heads,
+                          int32_t sink_tokens, int32_t max_budget, int32_t* indices, int32_t* counts, void* hip_stream) {
+  if (!seq_lens || !budgets || !indices || !counts) return PILLAR_EINVAL;
+  if (batch < 1 || num_kv_heads < 1 || max_budget < 1 || sink_tokens < 0) return PILLAR_EINVAL;
+  return launch_window_indices(seq_lens, budgets, batch, num_kv_heads, sink_tokens, max_budget, indices, counts,
+                               static_cast<hipStream_t>(hip_stream)) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+}
+
+int pillar_extend_indices(int32_t* indices, int32_t* counts, const int32_t* first_new, const int32_t* n_new,
+                          int32_t batch, int32_t num_kv_heads, int32_t max_budget, void* hip_stream) {
+  if (!indices || !counts || !first_new || !n_new) return PILLAR_EINVAL;
+  if (batch < 1 || num_kv_heads < 1 || max_budget < 1) return PILLAR_EINVAL;
+  return launch_extend_indices(indices, counts, first_new, n_new, batch, num_kv_heads, max_budget,
+                               static_cast<hipStream_t>(hip_stream)) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+}
+
 int pillar_set_option(const char* name, int64_t value) {
   if (!name || value < 0) return PILLAR_EINVAL;
   Options& o = options();

@@ -165,6 +165,36 @@ def test_verify_select_reduced_configs():
         _same_as_two_calls(gen.make_workload(cfg, batch=batch), f"fused select config{cfg}[:{batch}]")
 
 
+# -------------------------------------------- index lists from other sources ----
+def test_window_and_tail_lists_match_the_oracle_and_feed_the_draft():
+    """Static sink + window lists and the post-verification tail: integer-exact against the oracle,
+    and the draft kernel on those lists against the oracle's sparse attention."""
+    rng = np.random.default_rng(11)
+    lens = [3, 40, 517, 2049, 64]
+    w = small(130, B=5, Hq=16, Hkv=4, spec_k=2, seq_lens=lens, budgets=[8, 12, 64, 128, 64])
+    run = GpuRun(w)
+    pa.pillar_window_indices(run.dw.kv.seq_lens, run.dw.budgets, w.Hkv, 4, run.max_budget, run.indices, run.counts)
+    torch.cuda.synchronize()
+    want_idx, want_cnt = oracle.window_indices(w.seq_lens, w.budgets, w.Hkv, 4, max_budget=run.max_budget)
+    assert np.array_equal(run.counts.cpu().numpy(), want_cnt)
+    assert np.array_equal(run.indices.cpu().numpy(), want_idx)
+    # the tail: pretend the last tokens of each request were generated after the lists were made
+    n_new = np.array([1, 2, 0, 2, 70], dtype=np.int32)
+    first_new = (w.seq_lens - np.minimum(n_new, w.seq_lens)).astype(np.int32)
+    pa.pillar_extend_indices(run.indices, run.counts, torch.from_numpy(first_new).to(run.dev), torch.from_numpy(n_new).to(run.dev))
+    torch.cuda.synchronize()
+    ext_idx, ext_cnt = oracle.extend_indices(want_idx, want_cnt, first_new, n_new)
+    got_idx, got_cnt = run.indices.cpu().numpy(), run.counts.cpu().numpy()
+    assert np.array_equal(got_cnt, ext_cnt)
+    for b in range(w.B):
+        assert np.array_equal(got_idx[b, :, :ext_cnt[b]], ext_idx[b, :, :ext_cnt[b]]), f"request {b}"
+    run.decode()
+    torch.cuda.synchronize()
+    want_out, want_lse = oracle.sparse_decode(w, ext_idx, ext_cnt)
+    check_out(to_f64(run.d_out), want_out, w.kv_dtype, "draft on window + tail lists")
+    assert np.abs(run.d_lse.cpu().numpy() - want_lse).max() < LSE_ABS
+
+
 # ----------------------------------------------------------- edge cases ------
 def test_outputs_are_bit_identical_from_run_to_run():
     w = small(201, seq_lens=[40, 300, 1500], budgets=[8, 30, 100])
