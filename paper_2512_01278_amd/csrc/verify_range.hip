@@ -252,17 +252,9 @@ __device__ __forceinline__ Cursor open_cursor(const KvView& kv, const RangeWs& w
   return c;
 }
 
-// Issues the next tile of the stream into a register set and steps the cursor.
-template <bool FP8, bool WITH_V>
-__device__ __forceinline__ Flight issue_next(const KvView& kv, Cursor& c, const LaneGeom<FP8>& geo, int lane,
-                                             u32x4 (&rk)[TileRegs<FP8>::kLoads], u32x4 (&rv)[TileRegs<FP8>::kLoads]) {
-  Flight f;
-  f.valid = c.live;
-  f.sg = c.sg;
-  f.tb = c.tile * kTileTokens;
-  f.pages[0] = f.pages[1] = 0;
-  if (!c.live) return f;
-  issue_tile<FP8, true, WITH_V>(kv, c.sg, f.tb, c.pw, geo, lane, rk, rv, f.pages);
+// Steps the cursor past the tile just issued; entering the next pair costs no wait (its pages were
+// fetched one pair earlier).
+__device__ __forceinline__ void advance_cursor(const KvView& kv, Cursor& c, int lane) {
   c.tile += 1;
   c.unit += 1;
   if (c.unit >= c.end) {
@@ -287,6 +279,20 @@ __device__ __forceinline__ Flight issue_next(const KvView& kv, Cursor& c, const 
     c.pw.pg_b = load_window(kv, c.sg.b, 1, lane);
     prefetch_following(kv, c, lane);
   }
+}
+
+// Issues the next tile of the stream into a register set and steps the cursor.
+template <bool FP8, bool WITH_V>
+__device__ __forceinline__ Flight issue_next(const KvView& kv, Cursor& c, const LaneGeom<FP8>& geo, int lane,
+                                             u32x4 (&rk)[TileRegs<FP8>::kLoads], u32x4 (&rv)[TileRegs<FP8>::kLoads]) {
+  Flight f;
+  f.valid = c.live;
+  f.sg = c.sg;
+  f.tb = c.tile * kTileTokens;
+  f.pages[0] = f.pages[1] = 0;
+  if (!c.live) return f;
+  issue_tile<FP8, true, WITH_V>(kv, c.sg, f.tb, c.pw, geo, lane, rk, rv, f.pages);
+  advance_cursor(kv, c, lane);
   return f;
 }
 
@@ -772,6 +778,279 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_flash_range(
   finish();
 }
 
+// ------------------------------------------ 3 and 4 row blocks: two wavefronts per range ----
+// With more than 32 query rows the accumulators of a wavefront leave room for one wavefront per
+// SIMD only, and the pass is bound by that wavefront's own instruction stream.  Here two
+// wavefronts share a range: both walk the same tile stream, each fetches one 16-token half of
+// every tile into the shared LDS tile, and each keeps the accumulators of its own row blocks
+// (blocks 0-1, and the rest).  Four workgroup barriers per tile order the use of the one buffer:
+// K halves written | S^T read | V halves written | O^T read.
+template <bool FP8> struct HalfRegs { static constexpr int kLoads = TileRegs<FP8>::kLoads / 2; };
+
+// pages of both 16-token groups of the tile at tb (the window only moves forward), loads of group `half` only
+template <bool FP8>
+__device__ __forceinline__ void issue_half(const KvView& kv, const Segment& sg, int tb, int half, PageWin& pw, const LaneGeom<FP8>& geo,
+                                           int lane, u32x4 (&rk)[HalfRegs<FP8>::kLoads], u32x4 (&rv)[HalfRegs<FP8>::kLoads],
+                                           int (&pages)[2]) {
+  constexpr int kPerGroup = HalfRegs<FP8>::kLoads;
+  const int esz = FP8 ? 1 : 2;
+  const int last_page = (sg.L - 1) >> kv.page_shift;
+#pragma unroll
+  for (int grp = 0; grp < 2; ++grp) {
+    const int lp = min((tb + 16 * grp) >> kv.page_shift, last_page);
+    if (lp / kWindowPages > pw.win) {          // wave-uniform
+      pw.pg_a = pw.pg_b;
+      pw.win += 1;
+      pw.pg_b = load_window(kv, sg.b, pw.win + 1, lane);
+    }
+    pages[grp] = __builtin_amdgcn_readlane(pw.pg_a, lp - pw.win * kWindowPages);
+  }
+  const int tok0 = tb + 16 * half;
+  const int page = half == 0 ? pages[0] : pages[1];
+  const int64_t base = (static_cast<int64_t>(page) * kv.stride_page + static_cast<int64_t>(sg.g) * kv.stride_head +
+                        static_cast<int64_t>(tok0 & (kv.page_size - 1)) * kv.stride_slot) * esz;
+  const char* gk = static_cast<const char*>(kv.k_pool) + base;
+  const char* gv = static_cast<const char*>(kv.v_pool) + base;
+#pragma unroll
+  for (int u = 0; u < kPerGroup; ++u) {
+    const uint32_t off = geo.lane_off + u * geo.row_step;
+    rk[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gk + off));
+    rv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gv + off));
+  }
+}
+
+template <bool FP8>
+__device__ __forceinline__ Flight issue_next_half(const KvView& kv, Cursor& c, int half, const LaneGeom<FP8>& geo, int lane,
+                                                  u32x4 (&rk)[HalfRegs<FP8>::kLoads], u32x4 (&rv)[HalfRegs<FP8>::kLoads]) {
+  Flight f;
+  f.valid = c.live;
+  f.sg = c.sg;
+  f.tb = c.tile * kTileTokens;
+  f.pages[0] = f.pages[1] = 0;
+  if (!c.live) return f;
+  issue_half<FP8>(kv, c.sg, f.tb, half, c.pw, geo, lane, rk, rv, f.pages);
+  advance_cursor(kv, c, lane);
+  return f;
+}
+
+template <bool FP8, bool IS_V>
+__device__ __forceinline__ void half_to_lds(const u32x4 (&regs)[HalfRegs<FP8>::kLoads], uint8_t* tile, int lane, int half) {
+  if constexpr (!FP8) {
+    const int c = lane & 15;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int r = 16 * half + 4 * u + (lane >> 4);
+      *reinterpret_cast<u32x4*>(tile + (IS_V ? v_lds_addr(r, c) : k_lds_addr(r, c))) = regs[u];
+    }
+  } else {
+    const int c = (lane & 7) * 2;          // 16 fp8 = two 16-byte bf16 chunks
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int r = 16 * half + 8 * u + (lane >> 3);
+      u32x4 lo, hi;
+      widen_fp8x16(regs[u], lo, hi);
+      *reinterpret_cast<u32x4*>(tile + (IS_V ? v_lds_addr(r, c) : k_lds_addr(r, c))) = lo;
+      *reinterpret_cast<u32x4*>(tile + (IS_V ? v_lds_addr(r, c + 1) : k_lds_addr(r, c + 1))) = hi;
+    }
+  }
+}
+
+// S^T of the tile for row blocks rb0 .. rb0+RBW-1, Q operand from LDS
+template <int RBW>
+__device__ __forceinline__ void tile_qk_ldsq_at(const uint8_t* ktile, const uint8_t* qtile, int R, int rb0, f32x4 (&acc)[2][RBW], int lane) {
+  const int n = lane & 15, g = lane >> 4;
+  int qrow[RBW];
+#pragma unroll
+  for (int rb = 0; rb < RBW; ++rb) qrow[rb] = min(16 * (rb0 + rb) + n, R);
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) acc[sub][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const bf16x8 a0 = as_bf16x8(*reinterpret_cast<const u32x4*>(ktile + k_lds_addr(n, 4 * s + g)));
+    const bf16x8 a1 = as_bf16x8(*reinterpret_cast<const u32x4*>(ktile + k_lds_addr(16 + n, 4 * s + g)));
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+      const bf16x8 b = as_bf16x8(*reinterpret_cast<const u32x4*>(qtile + k_lds_addr(qrow[rb], 4 * s + g)));
+      acc[0][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc[0][rb], 0, 0, 0);
+      acc[1][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc[1][rb], 0, 0, 0);
+    }
+    if (RBW > 1) __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// one of the two wavefronts: `half` = which 16 tokens of every tile it fetches, RB0 / RBW = its row blocks
+template <int RB, bool FP8, bool STASH, int RBW, int RB0>
+__device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t* q, int n_q, const RangeWs& ws, uint16_t* out,
+                                                uint8_t* s_tile, uint8_t* s_q, int half) {
+  constexpr int kPairThreads = 2 * kThreads;
+  const int lane = threadIdx.x & (kThreads - 1);
+  const int n = lane & 15, g4 = lane >> 4;
+  const int G = kv.num_q_heads / kv.num_kv_heads;
+  const int R = n_q * G;
+  const int nv = R - 16 * (RB - 1);
+  const int tile_lanes = (RB - 1) * 64 + 4 * nv;
+  const float c2 = kv.sm_scale * kLog2e;
+  const LaneGeom<FP8> geo = lane_geom<FP8>(kv, lane);
+  constexpr int kHalf = HalfRegs<FP8>::kLoads;
+  constexpr int kRowsPerLoad = FP8 ? 8 : 4;
+  constexpr int kQIters = ((RB * 16 + 1) * 16 + kPairThreads - 1) / kPairThreads;
+  Cursor cur = open_cursor(kv, ws, lane);
+  if (!cur.live) return;                       // the same for both wavefronts
+  int unit = cur.unit;
+  u32x4 rk[kHalf], rv[kHalf];
+  Flight f = issue_next_half<FP8>(kv, cur, half, geo, lane, rk, rv);
+  Segment cs = f.sg;
+  bool started = false;
+  float m_run[RBW], l_run[RBW];
+  f32x4 o[RBW][8];
+  auto finish = [&]() {
+    const bool whole = cs.tile0 == 0 && cs.tile1 == cs.tiles;
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+      const float l = sum_over_groups(l_run[rb]);
+      const int r = 16 * (RB0 + rb) + n;
+      if (g4 == 0) {
+        ws.part_m[static_cast<int64_t>(cs.slot) * (RB * 16) + r] = m_run[rb];
+        ws.part_l[static_cast<int64_t>(cs.slot) * (RB * 16) + r] = l;
+      }
+      if (r >= R) continue;
+      if (whole) {
+        const float inv = 1.0f / l;
+        const int i = r / G, hg = r - i * G;
+        uint16_t* dst = out + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+          u32x2 pk;
+          pk.x = pack2(o[rb][db][0] * inv, o[rb][db][1] * inv);
+          pk.y = pack2(o[rb][db][2] * inv, o[rb][db][3] * inv);
+          *reinterpret_cast<u32x2*>(dst + 16 * db + 4 * g4) = pk;
+        }
+      } else {
+        float* dst = ws.part_o + (static_cast<int64_t>(cs.slot) * R + r) * kHeadDim + 4 * g4;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + 16 * db) = o[rb][db];
+      }
+    }
+  };
+  while (f.valid) {
+    __syncthreads();                           // the previous tile's V rows have been read by both wavefronts
+    if (!started || f.sg.slot != cs.slot) {    // workgroup-uniform: the stream has entered another pair
+      if (started) finish();
+      cs = f.sg;
+      started = true;
+      {                                        // Q rows of the pair -> LDS, by both wavefronts (row R is the zero row)
+        u32x4 qtmp[kQIters];
+#pragma unroll
+        for (int j = 0; j < kQIters; ++j) {
+          const int ch = static_cast<int>(threadIdx.x) + kPairThreads * j;
+          const int r = ch >> 4, c = ch & 15;
+          u32x4 v = {0u, 0u, 0u, 0u};
+          if (r < R) {
+            const int i = r / G, hg = r - i * G;
+            v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim + 8 * c);
+          }
+          qtmp[j] = v;
+        }
+#pragma unroll
+        for (int j = 0; j < kQIters; ++j) {
+          const int ch = static_cast<int>(threadIdx.x) + kPairThreads * j;
+          if (ch < (R + 1) * 16) *reinterpret_cast<u32x4*>(s_q + k_lds_addr(ch >> 4, ch & 15)) = qtmp[j];
+        }
+      }
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb) {
+        m_run[rb] = -INFINITY;
+        l_run[rb] = 0.f;
+#pragma unroll
+        for (int d = 0; d < 8; ++d) o[rb][d] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+    const int tb = f.tb;
+    half_to_lds<FP8, false>(rk, s_tile, lane, half);
+    float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
+    if constexpr (FP8) { half_scales(kv, cs.g, f.pages, kv.k_scale, ks); half_scales(kv, cs.g, f.pages, kv.v_scale, vs); }
+    __syncthreads();                           // the K tile (and Q) is complete
+    f32x4 s[2][RBW];
+    tile_qk_ldsq_at<RBW>(s_tile, s_q, R, RB0, s, lane);
+    if (tb + kTileTokens > cs.L) {
+#pragma unroll
+      for (int u = 0; u < kHalf; ++u)
+        if (tb + 16 * half + kRowsPerLoad * u + geo.row >= cs.L) rv[u] = u32x4{0u, 0u, 0u, 0u};
+    }
+    __syncthreads();                           // both wavefronts have read the K rows
+    half_to_lds<FP8, true>(rv, s_tile, lane, half);
+    f = issue_next_half<FP8>(kv, cur, half, geo, lane, rk, rv);
+    const bool edge = tb + kTileTokens > cs.L - n_q;
+    bf16x8 p[RBW];
+    uint8_t* st_base = ws.stash + static_cast<int64_t>(unit) * tile_lanes * 16;
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+      f32x4 pr[2] = {s[0][rb], s[1][rb]};
+      if (edge) {
+        const int r = 16 * (RB0 + rb) + n;
+        const int last = cs.L - n_q + (r < R ? r / G : n_q - 1);
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (tb + 16 * sub + 4 * g4 + i > last) pr[sub][i] = -INFINITY;
+      }
+      const float sc0 = c2 * ks[0], sc1 = c2 * ks[1];
+      float mx = fmaxf(fmaxf(fmaxf(pr[0][0], pr[0][1]), fmaxf(pr[0][2], pr[0][3])) * sc0,
+                       fmaxf(fmaxf(pr[1][0], pr[1][1]), fmaxf(pr[1][2], pr[1][3])) * sc1);
+      mx = max_over_groups(mx);
+      const float m_new = fmaxf(m_run[rb], mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      if (__any(m_new > m_run[rb])) {
+        const float alpha = fast_exp2(m_run[rb] - m_use);
+        l_run[rb] *= alpha;
+#pragma unroll
+        for (int d = 0; d < 8; ++d) o[rb][d] *= alpha;
+      }
+      m_run[rb] = m_new;
+      float sum = 0.f;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          pr[sub][i] = fast_exp2(fmaf(pr[sub][i], sub == 0 ? sc0 : sc1, -m_use));
+          sum += pr[sub][i];
+        }
+      l_run[rb] += sum;
+      const int sl = STASH ? stash_lane(RB0 + rb, RB, nv, n, g4, lane) : -1;
+      if (sl >= 0) {
+        uint32_t c[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) c[k] = stash_encode(pr[k >> 2][k & 3]);
+        u32x4 packed;
+        packed.x = c[0] | (c[1] << 16);
+        packed.y = c[2] | (c[3] << 16);
+        packed.z = c[4] | (c[5] << 16);
+        packed.w = c[6] | (c[7] << 16);
+        *reinterpret_cast<u32x4*>(st_base + sl * 16) = packed;
+      }
+      if (STASH && g4 == 0) ws.m_ref[static_cast<int64_t>(unit) * (RB * 16) + 16 * (RB0 + rb) + n] = m_use;
+      if constexpr (FP8) { pr[0] *= vs[0]; pr[1] *= vs[1]; }
+      p[rb] = pack_p(pr[0], pr[1]);
+    }
+    __syncthreads();                           // the V tile is complete
+    tile_pv<RBW>(s_tile, p, o, lane);
+    unit += 1;
+  }
+  finish();
+}
+
+template <int RB, bool FP8, bool STASH>
+__global__ __launch_bounds__(2 * kThreads, 2) void verify_flash_pair(KvView kv, const uint16_t* q, int n_q, RangeWs ws, uint16_t* out) {
+  static_assert(RB >= 3, "two wavefronts per range are for 3 and 4 row blocks");
+  __shared__ __attribute__((aligned(16))) uint8_t s_tile[kVTileBytes];
+  __shared__ __attribute__((aligned(16))) uint8_t s_q[(RB * 16 + 1) * kKRow];
+  if (threadIdx.x < kThreads) flash_pair_wave<RB, FP8, STASH, 2, 0>(kv, q, n_q, ws, out, s_tile, s_q, 0);
+  else flash_pair_wave<RB, FP8, STASH, RB - 2, 2>(kv, q, n_q, ws, out, s_tile, s_q, 1);
+}
+
 // Probabilities from the stash: one wavefront per stretch of tiles, two tiles in flight.
 template <int RB>
 __global__ __launch_bounds__(kThreads, RB <= 2 ? 8 : 6) void verify_score_finalize(KvView kv, int n_q, RangeWs ws, float* scores,
@@ -1058,11 +1337,18 @@ hipError_t run(const VerifyArgs& a, hipStream_t st) {
   if (options().verify_mode == 0 || !a.scores || a.select) {
     {
       KernelTimer t("verify_flash_range", st);
-      constexpr int kDepth = RB >= 3 && FP8 ? 2 : 1;
-      if (a.scores || a.select)
-        hipLaunchKernelGGL((verify_flash_range<RB, FP8, kDepth, true>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
-      else                                     // plain multi-query decode: nothing is stashed, nothing rebuilt
-        hipLaunchKernelGGL((verify_flash_range<RB, FP8, kDepth, false>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
+      const bool stash = a.scores || a.select;
+      if constexpr (RB >= 3) {                 // two wavefronts per range
+        if (stash)
+          hipLaunchKernelGGL((verify_flash_pair<RB, FP8, true>), dim3(ws.n_ranges), dim3(2 * kThreads), 0, st, kv, q, a.n_q, ws, out);
+        else                                   // plain multi-query decode: nothing is stashed, nothing rebuilt
+          hipLaunchKernelGGL((verify_flash_pair<RB, FP8, false>), dim3(ws.n_ranges), dim3(2 * kThreads), 0, st, kv, q, a.n_q, ws, out);
+      } else {
+        if (stash)
+          hipLaunchKernelGGL((verify_flash_range<RB, FP8, 1, true>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
+        else
+          hipLaunchKernelGGL((verify_flash_range<RB, FP8, 1, false>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
+      }
     }
     {
       KernelTimer t("verify_lse_combine", st);
