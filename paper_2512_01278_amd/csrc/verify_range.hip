@@ -609,13 +609,10 @@ __device__ __forceinline__ int stash_lane(int rb, int nblocks, int nv, int n, in
   return rb < nblocks - 1 ? rb * 64 + lane : (n < nv ? (nblocks - 1) * 64 + g4 * nv + n : -1);
 }
 
-// DEPTH tiles travel per wavefront: one where two wavefronts share a SIMD's registers; two for fp8 tiles
-// (half the bytes) where a wavefront has the SIMD to itself (3 and more row blocks).  Measured: depth 2
-// helps fp8 with 40 rows by 3 % and hurts bf16 with 36 rows by 4 %: those kernels are bound by their
-// own instruction stream, not by bytes in flight.
-template <int RB, bool FP8, int DEPTH, bool STASH>
-__global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_flash_range(KvView kv, const uint16_t* q, int n_q, RangeWs ws,
-                                                                                 uint16_t* out) {
+template <int RB, bool FP8, bool STASH>
+__global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, const uint16_t* q, int n_q, RangeWs ws, uint16_t* out) {
+  static_assert(RB <= 2, "3 and 4 row blocks run verify_flash_pair");
+  constexpr int DEPTH = 1;                     // tiles in flight (two wavefronts share a SIMD's registers: no room for more)
   __shared__ __attribute__((aligned(16))) uint8_t s_tile[kVTileBytes];
   __shared__ __attribute__((aligned(16))) uint8_t s_q[(RB * 16 + 1) * kKRow];
   const int lane = threadIdx.x;
@@ -1043,12 +1040,15 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
 }
 
 template <int RB, bool FP8, bool STASH>
-__global__ __launch_bounds__(2 * kThreads, 2) void verify_flash_pair(KvView kv, const uint16_t* q, int n_q, RangeWs ws, uint16_t* out) {
-  static_assert(RB >= 3, "two wavefronts per range are for 3 and 4 row blocks");
+__global__ __launch_bounds__(2 * kThreads, RB >= 3 ? 2 : 3) void verify_flash_pair(KvView kv, const uint16_t* q, int n_q, RangeWs ws, uint16_t* out) {
+  static_assert(RB >= 2, "two wavefronts need two row blocks");
+  // (with 2 row blocks, one each at 3 wavefronts per SIMD, the pass took as long as the one-wavefront kernel:
+  // 518 against 523 us at batch 128, so that case keeps the simpler kernel)
+  constexpr int kFirst = (RB + 1) / 2;         // row blocks of the first wavefront
   __shared__ __attribute__((aligned(16))) uint8_t s_tile[kVTileBytes];
   __shared__ __attribute__((aligned(16))) uint8_t s_q[(RB * 16 + 1) * kKRow];
-  if (threadIdx.x < kThreads) flash_pair_wave<RB, FP8, STASH, 2, 0>(kv, q, n_q, ws, out, s_tile, s_q, 0);
-  else flash_pair_wave<RB, FP8, STASH, RB - 2, 2>(kv, q, n_q, ws, out, s_tile, s_q, 1);
+  if (threadIdx.x < kThreads) flash_pair_wave<RB, FP8, STASH, kFirst, 0>(kv, q, n_q, ws, out, s_tile, s_q, 0);
+  else flash_pair_wave<RB, FP8, STASH, RB - kFirst, kFirst>(kv, q, n_q, ws, out, s_tile, s_q, 1);
 }
 
 // Probabilities from the stash: one wavefront per stretch of tiles, two tiles in flight.
@@ -1345,9 +1345,9 @@ hipError_t run(const VerifyArgs& a, hipStream_t st) {
           hipLaunchKernelGGL((verify_flash_pair<RB, FP8, false>), dim3(ws.n_ranges), dim3(2 * kThreads), 0, st, kv, q, a.n_q, ws, out);
       } else {
         if (stash)
-          hipLaunchKernelGGL((verify_flash_range<RB, FP8, 1, true>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
+          hipLaunchKernelGGL((verify_flash_range<RB, FP8, true>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
         else
-          hipLaunchKernelGGL((verify_flash_range<RB, FP8, 1, false>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
+          hipLaunchKernelGGL((verify_flash_range<RB, FP8, false>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
       }
     }
     {
