@@ -1371,8 +1371,7 @@ hipError_t run(const VerifyArgs& a, hipStream_t st) {
                        a.score_stride, sel);                                                                                \
   }
       if (kv.max_seq_len <= kSelectThreads * 8) PILLAR_SELECT(8)
-      else if (kv.max_seq_len <= kSelectThreads * 16) PILLAR_SELECT(16)
-      else PILLAR_SELECT(32)
+      else PILLAR_SELECT(16)
 #undef PILLAR_SELECT
     } else if (a.scores) {
       KernelTimer t("verify_score_finalize", st);
@@ -1427,7 +1426,9 @@ bool verify_range_supported(const VerifyArgs& a) {
 }
 
 bool verify_select_fused(const VerifyArgs& a) {
-  return a.select && verify_range_supported(a) && options().verify_mode == 0 && a.kv.max_seq_len <= kSelectThreads * 32;
+  // rows of more than 16 K tokens would need 128 KB of LDS per workgroup, one workgroup per compute unit:
+  // measured slower than the two kernels (config 5: 167 against 139 us), so those take the two steps
+  return a.select && verify_range_supported(a) && options().verify_mode == 0 && a.kv.max_seq_len <= kSelectThreads * 16;
 }
 
 size_t verify_range_workspace(const KvView& kv, int n_q) {

@@ -161,7 +161,8 @@ def test_verify_select_equals_the_two_calls():
 
 
 def test_verify_select_reduced_configs():
-    for cfg, batch in [(3, 4), (5, 2)]:
+    # config 4's rows (28 K tokens) are longer than the finish kernel keeps on chip: two steps inside the library
+    for cfg, batch in [(3, 4), (5, 2), (4, 1)]:
         _same_as_two_calls(gen.make_workload(cfg, batch=batch), f"fused select config{cfg}[:{batch}]")
 
 
