@@ -60,6 +60,15 @@ def test_many_tiny_requests_span_ranges():
     round_trip(w, what="300 tiny requests")
 
 
+def test_batch_larger_than_one_planning_pass():
+    """1100 requests: the unit prefix is built in two passes of 1024 and a range's first request is found
+    through a prefix longer than one wavefront-wide search step."""
+    rng = np.random.default_rng(9)
+    lens = rng.integers(3, 40, size=1100).tolist()
+    w = small(115, B=1100, Hq=4, Hkv=1, spec_k=2, seq_lens=lens, budgets=[4] * 1100)
+    round_trip(w, what="1100 tiny requests")
+
+
 def test_few_wide_ranges_cross_pairs_and_page_windows():
     """One wavefront per compute unit: every range then covers several (request, head) pairs and
     more than the 64 pages a lane register holds, so segments, partial slots and page windows change
@@ -158,6 +167,15 @@ def test_verify_select_equals_the_two_calls():
     # shapes the matrix-core path does not take go through the two calls inside the library
     _same_as_two_calls(small(125, q_dtype="f32", kv_dtype="f32", D=64), "fused select, generic path")
     _same_as_two_calls(small(126, q_dtype="f32", kv_dtype="f32", D=64), "fused select, generic path, no scores", with_scores=False)
+
+
+def test_verify_select_with_the_two_pass_variant():
+    pa.pillar_set_option("verify_mode", 1)
+    try:
+        _same_as_two_calls(small(127, B=3, Hq=16, Hkv=4, spec_k=4, seq_lens=[40, 700, 2049], budgets=[8, 64, 128]),
+                           "select, fp32 probabilities")
+    finally:
+        pa.pillar_set_option("verify_mode", 0)
 
 
 def test_verify_select_reduced_configs():
