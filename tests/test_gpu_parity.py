@@ -214,6 +214,40 @@ def test_window_and_tail_lists_match_the_oracle_and_feed_the_draft():
     assert np.abs(run.d_lse.cpu().numpy() - want_lse).max() < LSE_ABS
 
 
+# ------------------------------------------------------ stream capture ------
+def test_step_replays_from_a_captured_graph():
+    """The entry points only enqueue kernels on the caller's stream: a whole step captured into a graph and
+    replayed gives, every time, exactly what the eager calls give (outputs are wiped between replays)."""
+    w = small(140, B=4, Hq=16, Hkv=4, spec_k=4, seq_lens=[40, 700, 2049, 333], budgets=[8, 64, 128, 32])
+    eager = GpuRun(w)
+    eager.run_all(fused_select=True)
+    run = GpuRun(w)
+    run.run_all(fused_select=True)              # first calls outside the capture (one-time function attributes)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run.verify_select()
+            run.decode()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (run.out, run.lse, run.scores, run.d_out, run.d_lse):
+            t.fill_(float("nan"))
+        run.indices.fill_(-7)
+        run.counts.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(run.out.view(torch.int16), eager.out.view(torch.int16)), f"replay {rep}: out"
+        assert torch.equal(run.lse, eager.lse), f"replay {rep}: lse"
+        assert torch.equal(run.indices, eager.indices) and torch.equal(run.counts, eager.counts), f"replay {rep}: selection"
+        assert torch.equal(run.d_out.view(torch.int16), eager.d_out.view(torch.int16)), f"replay {rep}: draft"
+        for b in range(w.B):
+            L = int(w.seq_lens[b])
+            assert torch.equal(run.scores[b, :, :L], eager.scores[b, :, :L]), f"replay {rep}: scores of request {b}"
+
+
 # ----------------------------------------------------------- edge cases ------
 def test_outputs_are_bit_identical_from_run_to_run():
     w = small(201, seq_lens=[40, 300, 1500], budgets=[8, 30, 100])
