@@ -1,17 +1,30 @@
-// Verification attention with the score statistic (paper Section 4.1) as two
+// Verification attention with the score statistic (paper Section 4.1) as
 // streaming passes over an evenly divided token range.
 //
 // The probability of a token needs the row's log-sum-exp over the WHOLE
-// context, so the context is visited twice:
-//   pass 1 (K only)   S^T = K Q^T on the matrix cores, running (max, sum) per
-//                     row -> one (m, l) per row and segment
+// context, which is known only after the last token.  Two ways round it live
+// here; kernel boundaries are the only synchronisation in both.
+//
+// Default, K read once:
+//   single pass       S^T = K Q^T and O^T = V^T P^T on the matrix cores the
+//                     flash-decoding way (running max and sum per row, one
+//                     unnormalised (m, l, O) partial per segment); the
+//                     exponentials e = exp2(s - m_tile) are left behind as
+//                     16-bit values (verify_flash_range; verify_flash_pair
+//                     with two wavefronts per range for more than 32 rows)
 //   combine           per (request, KV head): final log-sum-exp per row
-//   pass 2 (K and V)  p = exp2(s - lse) is the exact probability: the score
-//                     statistic (mean of p over the rows of the GQA group) is
-//                     written directly, and O = sum p V needs no running
-//                     maximum; segment partials of O add linearly
-//   merge             per (request, KV head) cut into several segments: O = sum
-// Kernel boundaries are the only synchronisation.
+//   finish            scores = mean over rows of e * exp2(m_tile - lse), read
+//                     back from the stash (verify_score_finalize), or the same
+//                     plus Top-K from on-chip scores (verify_select_finish)
+//   merge             O = sum over segments of exp2(m_seg - lse) O_seg
+//
+// Variant with fp32 probabilities, K read twice (option verify_mode 1):
+//   pass 1 (K only)   running (max, sum) per row -> (m, l) per row and segment
+//   combine           as above
+//   pass 2 (K and V)  p = exp2(s - lse) is the exact probability: the score is
+//                     written directly, and O needs no running maximum;
+//                     segment partials of O add linearly
+//   merge             O = sum of the partials
 //
 // Work division.  The unit of work is a tile of 32 tokens of one (request, KV
 // head) pair; all units are laid out pair-major (request, head, tile) and the
