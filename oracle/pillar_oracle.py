@@ -236,3 +236,23 @@ def extend_indices(indices, counts, first_new, n_new):
         idx[b, :, c:c + n] = (int(first_new[b]) + np.arange(n, dtype=np.int32))[None, :]
         cnt[b] = c + n
     return idx, cnt
+
+
+def append_kv(w, k_pool, v_pool, k_new, v_new):
+    """Writes the K/V rows of the n newest tokens of every request into paged
+    pools (the verification attends to speculative tokens whose rows are already
+    in the cache: append, then attend).  k_new, v_new: [B, n, Hkv, D] in the
+    pool's storage type; row i of request b belongs at position L_b - n + i, i.e.
+    page block_table[b, pos // P], slot pos % P.  Returns new pools.
+    """
+    k_out, v_out = np.array(k_pool, copy=True), np.array(v_pool, copy=True)
+    n = k_new.shape[1]
+    for b in range(w.B):
+        L = int(w.seq_lens[b])
+        for i in range(n):
+            pos = L - n + i
+            page, slot = int(w.block_table[b, pos // w.P]), pos % w.P
+            k_out[page, :, slot, :] = k_new[b, i]
+            v_out[page, :, slot, :] = v_new[b, i]
+    return k_out, v_out
+

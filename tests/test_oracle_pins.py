@@ -319,3 +319,26 @@ def test_extend_indices_by_hand():
     assert new_idx[1, 0].tolist() == [0, 1, 2, 3, 9, 20]
     assert idx[0, 0, 3] == -1                                                # inputs untouched
 
+
+def test_append_kv_restores_rows_read_back_through_the_block_table():
+    """Cut the newest rows out of a generated pool (poison them), append them again: the pool is back
+    bit for bit, and what gather_request (a different code path) reads is what was appended."""
+    w = gen.make_custom(name="append", seed=77, B=3, Hq=4, Hkv=2, D=8, P=4, spec_k=2, q_dtype="f32", kv_dtype="f32",
+                        seq_lens=[3, 9, 14], budgets=[2, 2, 2])
+    n = 3
+    k_new = np.zeros((w.B, n, w.Hkv, w.D), dtype=w.k_pool.dtype)
+    v_new = np.zeros_like(k_new)
+    k_cut, v_cut = w.k_pool.copy(), w.v_pool.copy()
+    for b in range(w.B):
+        k, v = oracle.gather_request(w, b)                  # [L, Hkv, D] float64, exact for f32 storage
+        L = int(w.seq_lens[b])
+        k_new[b], v_new[b] = k[L - n:], v[L - n:]
+        for pos in range(L - n, L):
+            page, slot = int(w.block_table[b, pos // w.P]), pos % w.P
+            k_cut[page, :, slot, :] = np.nan
+            v_cut[page, :, slot, :] = np.nan
+    k_back, v_back = oracle.append_kv(w, k_cut, v_cut, k_new, v_new)
+    assert np.array_equal(k_back.view(np.uint32), w.k_pool.view(np.uint32))
+    assert np.array_equal(v_back.view(np.uint32), w.v_pool.view(np.uint32))
+    assert np.isnan(k_cut).sum() > np.isnan(w.k_pool).sum()    # the cut really removed something
+
