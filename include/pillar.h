@@ -157,6 +157,16 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
                          const int32_t* counts, int32_t max_budget, void* out, float* lse,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The write that precedes a verification: the K/V rows of the n_new newest
+ * tokens of every request go into their pages (append, then attend:
+ * seq_lens already counts them).  k_new, v_new: device [B][n_new][Hkv][D] in
+ * kv_dtype; row i of request b is written at position seq_lens[b]-n_new+i
+ * (rows whose position would be negative are skipped).  WRITES into the pools
+ * that pillar_kv_t describes.  bf16 and fp32 pools only: an fp8 pool returns
+ * PILLAR_EUNSUPPORTED (its page scales would have to be recomputed). */
+int pillar_append_kv(const pillar_kv_t* kv, const void* k_new, const void* v_new,
+                     int32_t n_new, void* hip_stream);
+
 /* Index lists from other sources for pillar_sparse_decode (Section 4.2: at
  * page size 1 any token set is a list).
  *

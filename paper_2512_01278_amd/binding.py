@@ -23,7 +23,7 @@ DTYPE_CODE = {"f32": PILLAR_F32, "bf16": PILLAR_BF16, "fp8_e4m3": PILLAR_FP8_E4M
 
 EXPORTS = ("pillar_version", "pillar_status_string", "pillar_workspace_bytes", "pillar_verify_attn",
            "pillar_verify_select", "pillar_select_topk", "pillar_sparse_decode", "pillar_window_indices",
-           "pillar_extend_indices", "pillar_profile_enable", "pillar_profile_reset",
+           "pillar_extend_indices", "pillar_append_kv", "pillar_profile_enable", "pillar_profile_reset",
            "pillar_profile_read", "pillar_set_option")
 
 
@@ -82,6 +82,8 @@ def load() -> C.CDLL:
     lib.pillar_sparse_decode.restype = C.c_int
     lib.pillar_sparse_decode.argtypes = [C.POINTER(pillar_kv_t), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.pillar_append_kv.restype = C.c_int
+    lib.pillar_append_kv.argtypes = [C.POINTER(pillar_kv_t), C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
     lib.pillar_window_indices.restype = C.c_int
     lib.pillar_window_indices.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                           C.c_void_p, C.c_void_p]
@@ -210,6 +212,12 @@ def pillar_sparse_decode(kv: KvCache, q: torch.Tensor, indices: torch.Tensor, co
     rc = load().pillar_sparse_decode(C.byref(s), q.data_ptr(), indices.data_ptr(), counts.data_ptr(), max_budget,
                                      out.data_ptr(), _ptr(lse), _ptr(workspace), wsz, _stream(stream))
     _check(rc, "pillar_sparse_decode")
+
+
+def pillar_append_kv(kv: KvCache, k_new: torch.Tensor, v_new: torch.Tensor, stream=None) -> None:
+    s = kv.c_struct()
+    _check(load().pillar_append_kv(C.byref(s), k_new.data_ptr(), v_new.data_ptr(), k_new.shape[1], _stream(stream)),
+           "pillar_append_kv")
 
 
 def pillar_window_indices(seq_lens: torch.Tensor, budgets: torch.Tensor, num_kv_heads: int, sink_tokens: int,

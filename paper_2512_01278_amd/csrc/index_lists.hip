@@ -7,12 +7,15 @@
 //   extend   tokens generated after the last verification have no score yet,
 //            but a draft step must see them: their positions are appended to
 //            every head's list.
+// And the write that precedes a verification: the K/V rows of the newest
+// tokens go into their pages (append, then attend).
 #include "launch.hpp"
 
 namespace pillar {
 namespace {
 
 constexpr int kThreads = 256;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __global__ __launch_bounds__(kThreads) void window_indices(const int32_t* seq_lens, const int32_t* budgets, int num_kv_heads,
                                                            int sink_tokens, int max_budget, int32_t* indices, int32_t* counts) {
@@ -40,7 +43,35 @@ __global__ __launch_bounds__(kThreads) void extend_indices(int32_t* indices, int
   if (threadIdx.x == 0) counts[b] = c + n;
 }
 
+// one workgroup per (request, new token): its Hkv rows of K and of V, 16 bytes per thread and step
+__global__ __launch_bounds__(kThreads) void append_kv(KvView kv, const uint8_t* k_new, const uint8_t* v_new, int n_new, int esz) {
+  const int b = blockIdx.y, i = blockIdx.x;
+  const int pos = kv.seq_lens[b] - n_new + i;
+  if (pos < 0) return;
+  const int page = kv.block_table[static_cast<int64_t>(b) * kv.block_table_stride + (pos >> kv.page_shift)];
+  const int slot = pos & (kv.page_size - 1);
+  const int row_bytes = kv.head_dim * esz;                       // a multiple of 16
+  const int chunks = row_bytes / 16;
+  uint8_t* kp = static_cast<uint8_t*>(const_cast<void*>(kv.k_pool));
+  uint8_t* vp = static_cast<uint8_t*>(const_cast<void*>(kv.v_pool));
+  for (int e = threadIdx.x; e < kv.num_kv_heads * chunks; e += kThreads) {
+    const int g = e / chunks, c = e - g * chunks;
+    const int64_t src = ((static_cast<int64_t>(b) * n_new + i) * kv.num_kv_heads + g) * row_bytes + 16 * c;
+    const int64_t dst = (static_cast<int64_t>(page) * kv.stride_page + static_cast<int64_t>(g) * kv.stride_head +
+                         static_cast<int64_t>(slot) * kv.stride_slot) * esz + 16 * c;
+    *reinterpret_cast<u32x4*>(kp + dst) = *reinterpret_cast<const u32x4*>(k_new + src);
+    *reinterpret_cast<u32x4*>(vp + dst) = *reinterpret_cast<const u32x4*>(v_new + src);
+  }
+}
+
 }  // namespace
+
+hipError_t launch_append_kv(const KvView& kv, const void* k_new, const void* v_new, int n_new, int esz, hipStream_t s) {
+  KernelTimer t("append_kv", s);
+  hipLaunchKernelGGL(append_kv, dim3(n_new, kv.batch), dim3(kThreads), 0, s, kv, static_cast<const uint8_t*>(k_new),
+                     static_cast<const uint8_t*>(v_new), n_new, esz);
+  return hipGetLastError();
+}
 
 hipError_t launch_window_indices(const int32_t* seq_lens, const int32_t* budgets, int batch, int num_kv_heads, int sink_tokens,
                                  int max_budget, int32_t* indices, int32_t* counts, hipStream_t s) {

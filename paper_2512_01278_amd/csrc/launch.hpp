@@ -68,6 +68,7 @@ size_t verify_generic_workspace(const KvView& kv, int n_q);
 hipError_t launch_verify_generic(const VerifyArgs& a, hipStream_t s);
 hipError_t launch_decode_generic(const DecodeArgs& a, hipStream_t s);
 hipError_t launch_topk(const TopkArgs& a, hipStream_t s);
+hipError_t launch_append_kv(const KvView& kv, const void* k_new, const void* v_new, int n_new, int esz, hipStream_t s);
 hipError_t launch_window_indices(const int32_t* seq_lens, const int32_t* budgets, int batch, int num_kv_heads, int sink_tokens,
                                  int max_budget, int32_t* indices, int32_t* counts, hipStream_t s);
 hipError_t launch_extend_indices(int32_t* indices, int32_t* counts, const int32_t* first_new, const int32_t* n_new, int batch,

@@ -302,6 +302,22 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
   return launch_decode_generic(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
 }
 
+int pillar_append_kv(const pillar_kv_t* kv, const void* k_new, const void* v_new, int32_t n_new, void* hip_stream) {
+  const int rc = check_kv(kv);
+  if (rc != PILLAR_OK) return rc;
+  if (!k_new || !v_new || n_new < 1) return PILLAR_EINVAL;
+  if (kv->kv_dtype == PILLAR_FP8_E4M3) return PILLAR_EUNSUPPORTED;      // the page scales would have to be recomputed
+  const int esz = kv->kv_dtype == PILLAR_F32 ? 4 : 2;
+  const KvView v = make_view(kv);
+  // 16-byte pieces: rows and strides must be multiples of 16 bytes, bases aligned
+  if ((v.head_dim * esz) % 16 || (v.stride_page * esz) % 16 || (v.stride_head * esz) % 16 || (v.stride_slot * esz) % 16)
+    return PILLAR_EUNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(v.k_pool) | reinterpret_cast<uintptr_t>(v.v_pool) | reinterpret_cast<uintptr_t>(k_new) |
+       reinterpret_cast<uintptr_t>(v_new)) & 15u)
+    return PILLAR_EUNSUPPORTED;
+  return launch_append_kv(v, k_new, v_new, n_new, esz, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+}
+
 int pillar_window_indices(const int32_t* seq_lens, const int32_t* budgets, int32_t batch, int32_t num_kv_heads,
                           int32_t sink_tokens, int32_t max_budget, int32_t* indices, int32_t* counts, void* hip_stream) {
   if (!seq_lens || !budgets || !indices || !counts) return PILLAR_EINVAL;

@@ -214,6 +214,54 @@ def test_window_and_tail_lists_match_the_oracle_and_feed_the_draft():
     assert np.abs(run.d_lse.cpu().numpy() - want_lse).max() < LSE_ABS
 
 
+# ------------------------------------------------------------- KV append ------
+@pytest.mark.parametrize("kv_dtype,q_dtype,D", [("bf16", "bf16", 128), ("f32", "f32", 64)])
+def test_append_kv_then_verify(kv_dtype, q_dtype, D):
+    """Cut the rows of the k+1 newest tokens out of the pools on the GPU (poison them), append them
+    through the entry point: the pools are back bit for bit (as the oracle's append makes them), and the
+    whole round on them matches the oracle."""
+    w = small(150, B=4, Hq=8, Hkv=2, D=D, spec_k=3, q_dtype=q_dtype, kv_dtype=kv_dtype, seq_lens=[4, 130, 517, 64],
+              budgets=[4, 40, 64, 64])
+    n = w.n_q
+    run = GpuRun(w)
+    k_new = np.zeros((w.B, n, w.Hkv, w.D), dtype=w.k_pool.dtype)
+    v_new = np.zeros_like(k_new)
+    k_cut, v_cut = w.k_pool.copy(), w.v_pool.copy()
+    poison = np.array(0x7FC1 if kv_dtype == "bf16" else 0x7FC00001).astype(w.k_pool.dtype)
+    for b in range(w.B):
+        L = int(w.seq_lens[b])
+        for i in range(n):
+            pos = L - n + i
+            page, slot = int(w.block_table[b, pos // w.P]), pos % w.P
+            k_new[b, i], v_new[b, i] = w.k_pool[page, :, slot, :], w.v_pool[page, :, slot, :]
+            k_cut[page, :, slot, :] = poison
+            v_cut[page, :, slot, :] = poison
+    want_k, want_v = oracle.append_kv(w, k_cut, v_cut, k_new, v_new)
+    bits = lambda a: a.view(np.uint16 if kv_dtype == "bf16" else np.uint32)      # unused slots hold NaN patterns
+    assert np.array_equal(bits(want_k), bits(w.k_pool)) and np.array_equal(bits(want_v), bits(w.v_pool))
+    kv = run.dw.kv
+    kv.k_pool.view(torch.int16 if kv_dtype == "bf16" else torch.int32).copy_(torch.from_numpy(k_cut.view(np.int16 if kv_dtype == "bf16" else np.int32)))
+    kv.v_pool.view(torch.int16 if kv_dtype == "bf16" else torch.int32).copy_(torch.from_numpy(v_cut.view(np.int16 if kv_dtype == "bf16" else np.int32)))
+    to_dev = lambda x: torch.from_numpy(x.view(np.int16 if kv_dtype == "bf16" else np.int32)).to(run.dev)
+    pa.pillar_append_kv(kv, to_dev(k_new), to_dev(v_new))
+    torch.cuda.synchronize()
+    as_int = torch.int16 if kv_dtype == "bf16" else torch.int32
+    assert torch.equal(kv.k_pool.view(as_int).cpu(), torch.from_numpy(w.k_pool.view(np.int16 if kv_dtype == "bf16" else np.int32)))
+    assert torch.equal(kv.v_pool.view(as_int).cpu(), torch.from_numpy(w.v_pool.view(np.int16 if kv_dtype == "bf16" else np.int32)))
+    run.run_all()
+    rep = compare_with_oracle(w, run, None, "round after append")
+    print(f"[ok] append {kv_dtype}: {rep}", flush=True)
+
+
+def test_append_kv_refuses_fp8_pools():
+    w = small(151, kv_dtype="fp8_e4m3", Hq=16, Hkv=2, spec_k=2, seq_lens=[5, 255, 100], budgets=[5, 16, 16])
+    run = GpuRun(w)
+    fake = torch.zeros((w.B, 3, w.Hkv, w.D), dtype=torch.uint8, device=run.dev)
+    with pytest.raises(pa.PillarError) as e:
+        pa.pillar_append_kv(run.dw.kv, fake, fake)
+    assert e.value.status == pa.binding.PILLAR_EUNSUPPORTED
+
+
 # ------------------------------------------------------ stream capture ------
 def test_step_replays_from_a_captured_graph():
     """The entry points only enqueue kernels on the caller's stream: a whole step captured into a graph and
