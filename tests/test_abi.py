@@ -106,6 +106,14 @@ def test_bad_call_arguments_are_rejected(lib):
     assert vs(q=None) == pb.PILLAR_EINVAL and vs(budgets=None) == pb.PILLAR_EINVAL and vs(idx=None) == pb.PILLAR_EINVAL
     assert vs(cnt=None) == pb.PILLAR_EINVAL and vs(mb=0) == pb.PILLAR_EINVAL
     assert vs(ws=None) == pb.PILLAR_EWORKSPACE and vs(wsz=128) == pb.PILLAR_EWORKSPACE
+    assert lib.pillar_append_kv(C.byref(s), None, FAKE, 3, None) == pb.PILLAR_EINVAL
+    assert lib.pillar_append_kv(C.byref(s), FAKE, FAKE, 0, None) == pb.PILLAR_EINVAL
+    assert lib.pillar_append_kv(C.byref(good_kv(kv_dtype=pb.PILLAR_FP8_E4M3, k_scale=FAKE, v_scale=FAKE)), FAKE, FAKE, 3, None) \
+        == pb.PILLAR_EUNSUPPORTED
+    assert lib.pillar_window_indices(None, FAKE, 4, 8, 4, 64, FAKE, FAKE, None) == pb.PILLAR_EINVAL
+    assert lib.pillar_window_indices(FAKE, FAKE, 4, 8, -1, 64, FAKE, FAKE, None) == pb.PILLAR_EINVAL
+    assert lib.pillar_extend_indices(FAKE, FAKE, None, FAKE, 4, 8, 64, None) == pb.PILLAR_EINVAL
+    assert lib.pillar_extend_indices(FAKE, FAKE, FAKE, FAKE, 4, 8, 0, None) == pb.PILLAR_EINVAL
     sd = lambda **k: lib.pillar_sparse_decode(C.byref(s), k.get("q", FAKE), k.get("idx", FAKE), k.get("cnt", FAKE),
                                               k.get("mb", 256), k.get("out", FAKE), None, FAKE, 1 << 40, None)
     assert sd(q=None) == pb.PILLAR_EINVAL and sd(idx=None) == pb.PILLAR_EINVAL
