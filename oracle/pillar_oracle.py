@@ -96,7 +96,7 @@ def gather_request(w, b: int):
 
 
 # ---------------------------------------------------------------------------
-def verify_attn(w, requests=None):
+def verify_attn(w, requests=None, spec_lens=None):
     """Full attention of the verification step and the score statistic.
 
     Returns out [B, k+1, Hq, D], lse [B, k+1, Hq] (natural log) and
@@ -104,32 +104,39 @@ def verify_attn(w, requests=None):
     Query i of request b sits at position L_b-(k+1)+i and sees keys 0..that
     position.  scores[b, g, t] is the mean over the R=(k+1)*G rows of group g
     of the softmax probability the row puts on token t (zero where masked).
+
+    spec_lens (optional, one per request, each <= k): requests speculate
+    different numbers of tokens (Section 5.4 allows heterogeneous
+    configurations).  Request b then has k_b+1 queries, the first k_b+1 of its
+    k+1 query slots, query i at position L_b-(k_b+1)+i; its mean runs over
+    (k_b+1)*G rows; out and lse of the unused slots stay zero.
     """
-    B, n_q, Hq, Hkv, D = w.B, w.n_q, w.Hq, w.Hkv, w.D
+    B, n_q_max, Hq, Hkv, D = w.B, w.n_q, w.Hq, w.Hkv, w.D
     G = Hq // Hkv
-    R = n_q * G
     Lmax = int(w.seq_lens.max()) if B else 0
     q_all = decode_tensor(w.q, w.q_dtype)
-    out = np.zeros((B, n_q, Hq, D))
-    lse = np.zeros((B, n_q, Hq))
+    out = np.zeros((B, n_q_max, Hq, D))
+    lse = np.zeros((B, n_q_max, Hq))
     scores = np.zeros((B, Hkv, Lmax))
     for b in (range(B) if requests is None else requests):
         L = int(w.seq_lens[b])
+        n_q = n_q_max if spec_lens is None else int(spec_lens[b]) + 1
+        R = n_q * G
         k, v = gather_request(w, b)
         pos = L - n_q + np.arange(n_q)                    # position of query i
         visible = np.arange(L)[None, :] <= pos[:, None]   # [n_q, L]
         for g in range(Hkv):
             kg = k[:, g, :]                               # [L, D]
             vg = v[:, g, :]
-            qg = q_all[b, :, g * G:(g + 1) * G, :]        # [n_q, G, D]
+            qg = q_all[b, :n_q, g * G:(g + 1) * G, :]     # [n_q, G, D]
             s = w.sm_scale * np.einsum("ihd,td->iht", qg, kg)      # [n_q, G, L]
             s = np.where(visible[:, None, :], s, -np.inf)
             m = s.max(axis=-1, keepdims=True)
             e = np.exp(s - m)
             l = e.sum(axis=-1, keepdims=True)
             p = e / l                                     # rows sum to one
-            out[b, :, g * G:(g + 1) * G, :] = np.einsum("iht,td->ihd", p, vg)
-            lse[b, :, g * G:(g + 1) * G] = (m + np.log(l))[..., 0]
+            out[b, :n_q, g * G:(g + 1) * G, :] = np.einsum("iht,td->ihd", p, vg)
+            lse[b, :n_q, g * G:(g + 1) * G] = (m + np.log(l))[..., 0]
             scores[b, g, :L] = p.sum(axis=(0, 1)) / R
     return out, lse, scores
 

@@ -4,6 +4,7 @@ Each test names what fixes the expected value: a hand-derived example, an
 independent pure-Python writing of the same definitions, a closed form, an
 invariant, or a library routine on the un-paged tensors.
 """
+import copy
 import json
 import math
 import os
@@ -341,4 +342,35 @@ def test_append_kv_restores_rows_read_back_through_the_block_table():
     assert np.array_equal(k_back.view(np.uint32), w.k_pool.view(np.uint32))
     assert np.array_equal(v_back.view(np.uint32), w.v_pool.view(np.uint32))
     assert np.isnan(k_cut).sum() > np.isnan(w.k_pool).sum()    # the cut really removed something
+
+
+def test_per_request_speculative_lengths_reduce_to_uniform_runs():
+    """A request that speculates k_b tokens inside a batch laid out for k must get exactly what a batch
+    laid out for k_b gives it (same K/V, same first k_b+1 queries, shifted positions), and k_b = 0 is the
+    sparse decode over every token."""
+    w = gen.make_custom(name="hetero", seed=31, B=3, Hq=4, Hkv=2, D=8, P=4, spec_k=3, q_dtype="f32", kv_dtype="f32",
+                        seq_lens=[9, 14, 6], budgets=[2, 2, 2])
+    spec = np.array([1, 3, 0])
+    out, lse, scores = oracle.verify_attn(w, spec_lens=spec)
+    assert np.allclose(scores.sum(-1), 1.0, atol=1e-12)
+    for b in range(w.B):
+        kb = int(spec[b])
+        sub = copy.copy(w)                               # same pools and tables, queries re-laid for k_b
+        sub.spec_k = kb
+        sub.q = w.q[:, :kb + 1].copy()
+        o2, l2, s2 = oracle.verify_attn(sub, requests=[b])
+        assert np.array_equal(o2[b], out[b, :kb + 1]) and np.array_equal(l2[b], lse[b, :kb + 1])
+        assert np.array_equal(s2[b], scores[b])
+        assert not out[b, kb + 1:].any() and not lse[b, kb + 1:].any()
+    # k_b = 0: one query at the last position sees everything = sparse decode over all tokens
+    b = 2
+    L = int(w.seq_lens[b])
+    idx = np.full((w.B, w.Hkv, L), -1, dtype=np.int32)
+    idx[b] = np.arange(L)
+    cnt = np.zeros(w.B, dtype=np.int32)
+    cnt[b] = L
+    wd = copy.copy(w)
+    wd.q_draft = w.q[:, 0].copy()
+    d_out, d_lse = oracle.sparse_decode(wd, idx, cnt, requests=[b])
+    assert np.allclose(d_out[b], out[b, 0], atol=1e-12) and np.allclose(d_lse[b], lse[b, 0], atol=1e-12)
 
