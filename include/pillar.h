@@ -129,6 +129,23 @@ int pillar_verify_select(const pillar_kv_t* kv, const void* q, int32_t spec_len_
                          int32_t* indices, int32_t* counts,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Verification of requests that speculate different numbers of tokens
+ * (Section 5.4: heterogeneous request configurations).  spec_lens: device [B],
+ * 0 <= spec_lens[b] <= spec_len_max.  Request b has spec_lens[b]+1 queries, the
+ * first of its spec_len_max+1 slots in q / out / lse, query i at position
+ * seq_lens[b]-(spec_lens[b]+1)+i; its statistic is the mean over
+ * (spec_lens[b]+1)*G rows; out and lse of the unused slots are not written.
+ * With budgets / indices / counts non-NULL the critical tokens are selected as
+ * by pillar_verify_select (all three NULL and max_budget 0: no selection).
+ * Served by the matrix-core kernels only: bf16 queries, bf16 or fp8 KV,
+ * head_dim 128, pages of >= 16 tokens, default "verify_mode"; anything else
+ * returns PILLAR_EUNSUPPORTED. */
+int pillar_verify_hetero(const pillar_kv_t* kv, const void* q, int32_t spec_len_max,
+                         const int32_t* spec_lens, void* out, float* lse, float* scores,
+                         int64_t score_stride, const int32_t* budgets, int32_t max_budget,
+                         int32_t* indices, int32_t* counts,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Critical-token selection (Section 4.1: Top-K on the averaged scores).
  *   scores   as written by pillar_verify_attn (all >= 0).
  *   budgets  device [B]: sparsity budget K of each request (>= 0).

@@ -22,7 +22,7 @@ PILLAR_F32, PILLAR_BF16, PILLAR_FP8_E4M3 = 0, 1, 2
 DTYPE_CODE = {"f32": PILLAR_F32, "bf16": PILLAR_BF16, "fp8_e4m3": PILLAR_FP8_E4M3}
 
 EXPORTS = ("pillar_version", "pillar_status_string", "pillar_workspace_bytes", "pillar_verify_attn",
-           "pillar_verify_select", "pillar_select_topk", "pillar_sparse_decode", "pillar_window_indices",
+           "pillar_verify_select", "pillar_verify_hetero", "pillar_select_topk", "pillar_sparse_decode", "pillar_window_indices",
            "pillar_extend_indices", "pillar_append_kv", "pillar_profile_enable", "pillar_profile_reset",
            "pillar_profile_read", "pillar_set_option")
 
@@ -73,6 +73,10 @@ def load() -> C.CDLL:
                                        C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.pillar_verify_select.restype = C.c_int
     lib.pillar_verify_select.argtypes = [C.POINTER(pillar_kv_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.pillar_verify_hetero.restype = C.c_int
+    lib.pillar_verify_hetero.argtypes = [C.POINTER(pillar_kv_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_size_t, C.c_void_p]
     lib.pillar_select_topk.restype = C.c_int
@@ -191,6 +195,18 @@ def pillar_verify_select(kv: KvCache, q: torch.Tensor, spec_len_k: int, out: tor
                                      workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                      _stream(stream))
     _check(rc, "pillar_verify_select")
+
+
+def pillar_verify_hetero(kv: KvCache, q: torch.Tensor, spec_len_max: int, spec_lens: torch.Tensor, out: torch.Tensor,
+                         lse: Optional[torch.Tensor], scores: Optional[torch.Tensor], workspace: torch.Tensor,
+                         budgets: Optional[torch.Tensor] = None, max_budget: int = 0,
+                         indices: Optional[torch.Tensor] = None, counts: Optional[torch.Tensor] = None, stream=None) -> None:
+    s = kv.c_struct()
+    stride = scores.stride(1) if scores is not None else 0
+    rc = load().pillar_verify_hetero(C.byref(s), q.data_ptr(), spec_len_max, spec_lens.data_ptr(), out.data_ptr(), _ptr(lse),
+                                     _ptr(scores), stride, _ptr(budgets), max_budget, _ptr(indices), _ptr(counts),
+                                     workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "pillar_verify_hetero")
 
 
 def pillar_select_topk(scores: torch.Tensor, seq_lens: torch.Tensor, budgets: torch.Tensor,

@@ -39,6 +39,7 @@ struct VerifyArgs {
   int32_t q_dtype, kv_dtype;
   void* workspace;
   const SelectOut* select = nullptr;   // non-null: also select the Top-K of every (request, KV head)
+  const int32_t* spec_lens = nullptr;  // non-null: device [B], request b speculates spec_lens[b] <= n_q - 1 tokens
 };
 
 struct DecodeArgs {

@@ -153,8 +153,9 @@ size_t scratch_scores_bytes(const KvView& v) {
   return static_cast<size_t>(v.batch) * v.num_kv_heads * scratch_score_stride(v) * sizeof(float);
 }
 
-int verify_common(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, void* out, float* lse, float* scores,
-                  int64_t score_stride, const SelectOut* select, void* workspace, size_t workspace_bytes, void* hip_stream) {
+int verify_common(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, const int32_t* spec_lens, void* out, float* lse,
+                  float* scores, int64_t score_stride, const SelectOut* select, void* workspace, size_t workspace_bytes,
+                  void* hip_stream) {
   int rc = check_kv(kv);
   if (rc != PILLAR_OK) return rc;
   rc = check_spec(kv, spec_len_k);
@@ -173,6 +174,9 @@ int verify_common(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, void
   a.kv_dtype = kv->kv_dtype;
   a.workspace = workspace;
   a.select = select;
+  a.spec_lens = spec_lens;
+  // per-request speculative lengths exist in the matrix-core single-pass kernels only
+  if (spec_lens && (force_generic() || !verify_range_supported(a))) return PILLAR_EUNSUPPORTED;
   const size_t stage_ws = verify_workspace(a.kv, a.n_q);
   rc = check_workspace(workspace, workspace_bytes, stage_ws + (select ? scratch_scores_bytes(a.kv) : 0));
   if (rc != PILLAR_OK) return rc;
@@ -235,7 +239,7 @@ size_t pillar_workspace_bytes(const pillar_kv_t* kv, int32_t spec_len_k, int32_t
 int pillar_verify_attn(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, void* out, float* lse,
                        float* scores, int64_t score_stride, void* workspace, size_t workspace_bytes,
                        void* hip_stream) {
-  return verify_common(kv, q, spec_len_k, out, lse, scores, score_stride, nullptr, workspace, workspace_bytes, hip_stream);
+  return verify_common(kv, q, spec_len_k, nullptr, out, lse, scores, score_stride, nullptr, workspace, workspace_bytes, hip_stream);
 }
 
 int pillar_verify_select(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, void* out, float* lse,
@@ -248,7 +252,22 @@ int pillar_verify_select(const pillar_kv_t* kv, const void* q, int32_t spec_len_
   sel.max_budget = max_budget;
   sel.indices = indices;
   sel.counts = counts;
-  return verify_common(kv, q, spec_len_k, out, lse, scores, score_stride, &sel, workspace, workspace_bytes, hip_stream);
+  return verify_common(kv, q, spec_len_k, nullptr, out, lse, scores, score_stride, &sel, workspace, workspace_bytes, hip_stream);
+}
+
+int pillar_verify_hetero(const pillar_kv_t* kv, const void* q, int32_t spec_len_max, const int32_t* spec_lens, void* out,
+                         float* lse, float* scores, int64_t score_stride, const int32_t* budgets, int32_t max_budget,
+                         int32_t* indices, int32_t* counts, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!spec_lens) return PILLAR_EINVAL;
+  const bool want_select = budgets || indices || counts;
+  if (want_select && (!budgets || !indices || !counts || max_budget < 1)) return PILLAR_EINVAL;
+  SelectOut sel;
+  sel.budgets = budgets;
+  sel.max_budget = max_budget;
+  sel.indices = indices;
+  sel.counts = counts;
+  return verify_common(kv, q, spec_len_max, spec_lens, out, lse, scores, score_stride, want_select ? &sel : nullptr, workspace,
+                       workspace_bytes, hip_stream);
 }
 
 int pillar_select_topk(const float* scores, int64_t score_stride, const int32_t* seq_lens, const int32_t* budgets,

@@ -56,11 +56,15 @@ struct RangeWs {
   float* lse2;          // [pairs][rows_pad]      log2 domain
   uint8_t* stash;       // single-pass variant: [units][tile lanes][16 bytes]
   float* m_ref;         //                      [units][rows_pad] running maximum the stash of a tile refers to
+  const int32_t* spec_lens;   // [B] speculative length of each request, or null: all use the call's k
   int32_t rows_pad;     // 16 * row blocks
   int32_t n_ranges;     // N
 };
 
 __host__ __device__ inline int tiles_of_len(int len) { return (len + kTileTokens - 1) / kTileTokens; }
+
+// query positions of request b: all n_q slots, or as many as the request speculates
+__device__ __forceinline__ int queries_of(const RangeWs& ws, int b, int n_q) { return ws.spec_lens ? min(ws.spec_lens[b] + 1, n_q) : n_q; }
 
 // first unit of range w, and the range a unit falls in
 __device__ __forceinline__ int range_begin(int w, int total, int n) { return static_cast<int>(static_cast<int64_t>(w) * total / n); }
@@ -403,7 +407,6 @@ __global__ __launch_bounds__(256) void verify_lse_combine_range(KvView kv, int n
   const int pair = idx / rows, row = idx - pair * rows;
   const int b = pair / kv.num_kv_heads, g = pair - b * kv.num_kv_heads;
   const int G = kv.num_q_heads / kv.num_kv_heads;
-  const int R = n_q * G;
   const int total = ws.ctrl[0];
   const int tiles = tiles_of_len(kv.seq_lens[b]);
   const int u0 = ws.ureq[b] + g * tiles;
@@ -420,10 +423,11 @@ __global__ __launch_bounds__(256) void verify_lse_combine_range(KvView kv, int n
     l = l * fast_exp2(m - mu) + lc * fast_exp2(mc - mu);
     m = mn;
   }
-  // rows beyond R get +inf so that their probabilities vanish in the second pass
-  const float v = row < R ? m + log2f(l) : INFINITY;
+  // rows beyond the request's R get +inf so that their probabilities vanish where the log-sum-exp is applied
+  const int Rb = queries_of(ws, b, n_q) * G;
+  const float v = row < Rb ? m + log2f(l) : INFINITY;
   ws.lse2[idx] = v;
-  if (lse_out && row < R) {
+  if (lse_out && row < Rb) {
     const int i = row / G, hg = row - i * G;
     lse_out[(static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg] = v * kLn2;
   }
@@ -649,6 +653,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, con
   bool started = false;
   float m_run[RB], l_run[RB];
   f32x4 o[RB][8];
+  int nq_b = n_q, Rb = R;                      // query positions and rows of the current pair's request
   auto finish = [&]() {
     const bool whole = cs.tile0 == 0 && cs.tile1 == cs.tiles;
 #pragma unroll
@@ -660,7 +665,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, con
         ws.part_m[static_cast<int64_t>(cs.slot) * (RB * 16) + r] = m_run[rb];
         ws.part_l[static_cast<int64_t>(cs.slot) * (RB * 16) + r] = l;
       }
-      if (r >= R) continue;
+      if (r >= Rb) continue;               // rows of query slots the request does not use are left alone
       if (whole) {
         const float inv = 1.0f / l;
         const int i = r / G, hg = r - i * G;
@@ -684,6 +689,8 @@ __global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, con
       if (started) finish();
       cs = f.sg;
       started = true;
+      nq_b = __builtin_amdgcn_readfirstlane(queries_of(ws, cs.b, n_q));
+      Rb = nq_b * G;
       {                                        // Q rows of the pair -> LDS (row R is the zero row of the padding)
         u32x4 qtmp[kQIters];
 #pragma unroll
@@ -691,7 +698,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, con
           const int ch = lane + kThreads * j;
           const int r = ch >> 4, c = ch & 15;
           u32x4 v = {0u, 0u, 0u, 0u};
-          if (r < R) {
+          if (r < Rb) {
             const int i = r / G, hg = r - i * G;
             v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim + 8 * c);
           }
@@ -729,7 +736,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, con
       f32x4 pr[2] = {s[0][rb], s[1][rb]};
       if (edge) {
         const int r = 16 * rb + n;
-        const int last = cs.L - n_q + (r < R ? r / G : n_q - 1);
+        const int last = cs.L - nq_b + (r < Rb ? r / G : nq_b - 1);
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -915,6 +922,7 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
   bool started = false;
   float m_run[RBW], l_run[RBW];
   f32x4 o[RBW][8];
+  int nq_b = n_q, Rb = R;                      // query positions and rows of the current pair's request
   auto finish = [&]() {
     const bool whole = cs.tile0 == 0 && cs.tile1 == cs.tiles;
 #pragma unroll
@@ -925,7 +933,7 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
         ws.part_m[static_cast<int64_t>(cs.slot) * (RB * 16) + r] = m_run[rb];
         ws.part_l[static_cast<int64_t>(cs.slot) * (RB * 16) + r] = l;
       }
-      if (r >= R) continue;
+      if (r >= Rb) continue;               // rows of query slots the request does not use are left alone
       if (whole) {
         const float inv = 1.0f / l;
         const int i = r / G, hg = r - i * G;
@@ -950,6 +958,8 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
       if (started) finish();
       cs = f.sg;
       started = true;
+      nq_b = __builtin_amdgcn_readfirstlane(queries_of(ws, cs.b, n_q));
+      Rb = nq_b * G;
       {                                        // Q rows of the pair -> LDS, by both wavefronts (row R is the zero row)
         u32x4 qtmp[kQIters];
 #pragma unroll
@@ -957,7 +967,7 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
           const int ch = static_cast<int>(threadIdx.x) + kPairThreads * j;
           const int r = ch >> 4, c = ch & 15;
           u32x4 v = {0u, 0u, 0u, 0u};
-          if (r < R) {
+          if (r < Rb) {
             const int i = r / G, hg = r - i * G;
             v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim + 8 * c);
           }
@@ -1000,7 +1010,7 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
       f32x4 pr[2] = {s[0][rb], s[1][rb]};
       if (edge) {
         const int r = 16 * (RB0 + rb) + n;
-        const int last = cs.L - n_q + (r < R ? r / G : n_q - 1);
+        const int last = cs.L - nq_b + (r < Rb ? r / G : nq_b - 1);
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -1074,7 +1084,7 @@ __global__ __launch_bounds__(kThreads, RB <= 2 ? 8 : 6) void verify_score_finali
   const int R = n_q * G;
   const int nv = R - 16 * (RB - 1);
   const int tile_lanes = (RB - 1) * 64 + 4 * nv;
-  const float inv_r = 1.0f / static_cast<float>(R);
+  float inv_r = 1.0f / static_cast<float>(queries_of(ws, 0, n_q) * G);      // set per request below
   const int total = ws.ctrl[0];
   const int u0 = range_begin(blockIdx.x, total, gridDim.x), u1 = range_begin(blockIdx.x + 1, total, gridDim.x);
   if (u0 >= u1) return;
@@ -1089,6 +1099,7 @@ __global__ __launch_bounds__(kThreads, RB <= 2 ? 8 : 6) void verify_score_finali
   for (int rb = 0; rb < RB; ++rb) sl[rb] = stash_lane(rb, RB, nv, n, g4, lane);
   float lse2[RB];
   auto load_lse = [&]() {
+    inv_r = 1.0f / static_cast<float>(queries_of(ws, b, n_q) * G);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) lse2[rb] = ws.lse2[static_cast<int64_t>(b * kv.num_kv_heads + g) * (RB * 16) + 16 * rb + n];
   };
@@ -1167,7 +1178,8 @@ __global__ __launch_bounds__(256) void verify_o_merge_flash(KvView kv, int n_q, 
   const int u0 = ws.ureq[b] + g * tiles;
   const int w0 = range_of(u0, total, ws.n_ranges), w1 = range_of(u0 + tiles - 1, total, ws.n_ranges);
   if (w1 == w0) return;
-  for (int idx = threadIdx.x; idx < R * (kHeadDim / 4); idx += 256) {
+  const int Rb = queries_of(ws, b, n_q) * G;
+  for (int idx = threadIdx.x; idx < Rb * (kHeadDim / 4); idx += 256) {
     const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
     const float lse = ws.lse2[static_cast<int64_t>(pair) * ws.rows_pad + r];
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -1213,7 +1225,7 @@ __global__ __launch_bounds__(kSelectThreads) void verify_select_finish(KvView kv
   const int R = n_q * G;
   const int nv = R - 16 * (RB - 1);
   const int tile_lanes = (RB - 1) * 64 + 4 * nv;
-  const float inv_r = 1.0f / static_cast<float>(R);
+  const float inv_r = 1.0f / static_cast<float>(queries_of(ws, b, n_q) * G);
   int sl[RB];
   float lse2[RB];
 #pragma unroll
@@ -1330,6 +1342,7 @@ RangeWs carve(const KvView& kv, int n_q, void* workspace, size_t* total_bytes) {
   const size_t tile_lanes = (rpad / 16 - 1) * 64 + 4 * (R - (rpad - 16));
   w.stash = reinterpret_cast<uint8_t*>(take(units * tile_lanes * 16));
   w.m_ref = reinterpret_cast<float*>(take(units * rpad * 4));
+  w.spec_lens = nullptr;
   w.rows_pad = static_cast<int32_t>(rpad);
   w.n_ranges = static_cast<int32_t>(n);
   if (total_bytes) *total_bytes = off;
@@ -1339,7 +1352,8 @@ RangeWs carve(const KvView& kv, int n_q, void* workspace, size_t* total_bytes) {
 template <int RB, bool FP8>
 hipError_t run(const VerifyArgs& a, hipStream_t st) {
   const KvView& kv = a.kv;
-  const RangeWs ws = carve(kv, a.n_q, a.workspace, nullptr);
+  RangeWs ws = carve(kv, a.n_q, a.workspace, nullptr);
+  ws.spec_lens = a.spec_lens;
   const uint16_t* q = static_cast<const uint16_t*>(a.q);
   uint16_t* out = static_cast<uint16_t*>(a.out);
   const int pairs = kv.batch * kv.num_kv_heads;
@@ -1426,6 +1440,7 @@ bool verify_range_supported(const VerifyArgs& a) {
   if (kv.head_dim != kHeadDim || kv.page_size < 16) return false;
   if (row_blocks(kv, a.n_q) > 4) return false;
   if (!(kv.sm_scale > 0.f)) return false;       // the kernels take row maxima before scaling
+  if (a.spec_lens && options().verify_mode != 0) return false;   // per-request lengths: single-pass kernels only
   const int64_t align = a.kv_dtype == PILLAR_BF16 ? 8 : 16;      // elements per 16 bytes
   if (kv.stride_page % align || kv.stride_head % align || kv.stride_slot % align) return false;
   if ((reinterpret_cast<uintptr_t>(kv.k_pool) | reinterpret_cast<uintptr_t>(kv.v_pool) | reinterpret_cast<uintptr_t>(a.q) |

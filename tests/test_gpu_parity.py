@@ -214,6 +214,45 @@ def test_window_and_tail_lists_match_the_oracle_and_feed_the_draft():
     assert np.abs(run.d_lse.cpu().numpy() - want_lse).max() < LSE_ABS
 
 
+# ------------------------------------------- per-request speculative lengths ----
+def _hetero_case(w, spec, what, with_select):
+    run = GpuRun(w)
+    spec_dev = torch.from_numpy(spec.astype(np.int32)).to(run.dev)
+    if with_select:
+        pa.pillar_verify_hetero(run.dw.kv, run.dw.q, w.spec_k, spec_dev, run.out, run.lse, run.scores, run.workspace,
+                                budgets=run.dw.budgets, max_budget=run.max_budget, indices=run.indices, counts=run.counts)
+    else:
+        pa.pillar_verify_hetero(run.dw.kv, run.dw.q, w.spec_k, spec_dev, run.out, run.lse, run.scores, run.workspace)
+        run.topk()
+    torch.cuda.synchronize()
+    want_out, want_lse, want_scores = oracle.verify_attn(w, spec_lens=spec)
+    got_out, got_lse = to_f64(run.out), run.lse.cpu().numpy().astype(np.float64)
+    for b in range(w.B):
+        nq = int(spec[b]) + 1
+        check_out(got_out[b, :nq], want_out[b, :nq], w.kv_dtype, f"{what}: out of request {b}")
+        assert np.abs(got_lse[b, :nq] - want_lse[b, :nq]).max() < LSE_ABS, f"{what}: lse of request {b}"
+        assert np.isnan(got_out[b, nq:]).all(), f"{what}: unused query slots of request {b} were written"
+    from tests.harness import check_scores, check_topk_against_oracle_scores
+    worst = check_scores(run.scores.cpu().numpy(), want_scores, w.seq_lens, range(w.B), what)
+    check_topk_against_oracle_scores(run.indices.cpu().numpy(), run.counts.cpu().numpy(), want_scores, w.seq_lens, w.budgets,
+                                     range(w.B), what)
+    print(f"[ok] {what}: scores {worst:.2e}", flush=True)
+
+
+def test_requests_with_different_speculative_lengths():
+    w = small(160, B=5, Hq=16, Hkv=4, spec_k=4, seq_lens=[5, 700, 2049, 33, 1500], budgets=[4, 64, 128, 16, 64])
+    _hetero_case(w, np.array([4, 0, 2, 3, 1]), "hetero k", with_select=False)
+    _hetero_case(w, np.array([0, 4, 1, 0, 3]), "hetero k, fused selection", with_select=True)
+    w8 = small(161, kv_dtype="fp8_e4m3", Hq=16, Hkv=2, spec_k=4, seq_lens=[5, 255, 1000], budgets=[5, 16, 128])
+    _hetero_case(w8, np.array([2, 4, 0]), "hetero k, fp8, 40 rows", with_select=True)
+    with pytest.raises(pa.PillarError) as e:      # the generic kernels do not know per-request lengths
+        wf = small(162, q_dtype="f32", kv_dtype="f32", D=64)
+        r = GpuRun(wf)
+        pa.pillar_verify_hetero(r.dw.kv, r.dw.q, wf.spec_k, torch.zeros(wf.B, dtype=torch.int32, device=r.dev), r.out, r.lse,
+                                r.scores, r.workspace)
+    assert e.value.status == pa.binding.PILLAR_EUNSUPPORTED
+
+
 # ------------------------------------------------------------- KV append ------
 @pytest.mark.parametrize("kv_dtype,q_dtype,D", [("bf16", "bf16", 128), ("f32", "f32", 64)])
 def test_append_kv_then_verify(kv_dtype, q_dtype, D):
