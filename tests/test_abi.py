@@ -106,6 +106,13 @@ def test_bad_call_arguments_are_rejected(lib):
     assert vs(q=None) == pb.PILLAR_EINVAL and vs(budgets=None) == pb.PILLAR_EINVAL and vs(idx=None) == pb.PILLAR_EINVAL
     assert vs(cnt=None) == pb.PILLAR_EINVAL and vs(mb=0) == pb.PILLAR_EINVAL
     assert vs(ws=None) == pb.PILLAR_EWORKSPACE and vs(wsz=128) == pb.PILLAR_EWORKSPACE
+    vh = lambda **k: lib.pillar_verify_hetero(C.byref(k.get("kv", s)), FAKE, 4, k.get("spec", FAKE), FAKE, None, None, 0,
+                                              k.get("budgets", None), k.get("mb", 0), k.get("idx", None), k.get("cnt", None),
+                                              FAKE, 1 << 40, None)
+    assert vh(spec=None) == pb.PILLAR_EINVAL
+    assert vh(budgets=FAKE) == pb.PILLAR_EINVAL                      # selection wanted, but not all of its arguments
+    assert vh(budgets=FAKE, idx=FAKE, cnt=FAKE, mb=0) == pb.PILLAR_EINVAL
+    assert vh(kv=good_kv(q_dtype=pb.PILLAR_F32, kv_dtype=pb.PILLAR_F32)) == pb.PILLAR_EUNSUPPORTED   # generic kernels only
     assert lib.pillar_append_kv(C.byref(s), None, FAKE, 3, None) == pb.PILLAR_EINVAL
     assert lib.pillar_append_kv(C.byref(s), FAKE, FAKE, 0, None) == pb.PILLAR_EINVAL
     assert lib.pillar_append_kv(C.byref(good_kv(kv_dtype=pb.PILLAR_FP8_E4M3, k_scale=FAKE, v_scale=FAKE)), FAKE, FAKE, 3, None) \
