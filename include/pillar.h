@@ -20,7 +20,9 @@
  *     the call returns at once.  Scratch memory comes in through `workspace`
  *     (device, 256-byte aligned, at least pillar_workspace_bytes() bytes); its
  *     contents are meaningless between calls and calls sharing one workspace
- *     must be ordered on one stream.
+ *     must be ordered on one stream.  Calls can be captured into a HIP graph;
+ *     make one ordinary call with the same shapes first (the first launch of
+ *     a kernel may set a function attribute, which is not a stream operation).
  *   - Return value: PILLAR_OK or a negative pillar_status.  Argument errors
  *     are detected on the host before anything is launched, so a failed call
  *     has no effect on the device.  Page ids and token indices stored in
