@@ -45,6 +45,11 @@ def test_config1_tiny_fp32():
     (107, dict(q_dtype="f32", kv_dtype="bf16", spec_k=15, Hq=4, Hkv=1, seq_lens=[16, 17, 400], budgets=[3, 3, 3])),
     (108, dict(B=1, Hq=32, Hkv=8, spec_k=4, seq_lens=[2100], budgets=[128], sink_tokens=4)),
     (109, dict(kv_dtype="fp8_e4m3", q_dtype="f32", D=64, P=4, seq_lens=[3, 4, 333], budgets=[1, 4, 33])),
+    # the largest row counts of the matrix-core path: 64 rows (4 row blocks) from 16 queries x 4 heads and from
+    # 4 queries x 16 heads, 48 rows (3 row blocks) with fp8 KV
+    (116, dict(spec_k=15, Hq=8, Hkv=2, seq_lens=[16, 130, 1100], budgets=[16, 40, 64])),
+    (117, dict(spec_k=3, Hq=16, Hkv=1, seq_lens=[4, 257, 600], budgets=[4, 64, 64])),
+    (118, dict(kv_dtype="fp8_e4m3", spec_k=5, Hq=16, Hkv=2, seq_lens=[6, 255, 1000], budgets=[6, 16, 128])),
 ])
 def test_small_shapes(seed, kw):
     round_trip(small(seed, **kw))
