@@ -184,7 +184,7 @@ def make_custom(*, name: str, seed: int, B: int, Hq: int, Hkv: int, D: int, P: i
                 pillar_frac: float = 0.02, pillar_gain: float = 3.0,
                 pillars_per_request: int = 0, sink_tokens: int = 0,
                 sink_gain: float = 4.0, poison: bool = True,
-                extra_table_cols: int = 0) -> Workload:
+                extra_table_cols: int = 0, allow_short: bool = False) -> Workload:
     """Draw one workload.  Draw order (fixed, so a seed names the tensors):
     block table, Q, then per request K, V and pillar positions, then Q_draft.
 
@@ -202,7 +202,8 @@ def make_custom(*, name: str, seed: int, B: int, Hq: int, Hkv: int, D: int, P: i
     seq_lens = np.asarray(seq_lens, dtype=np.int32)
     budgets = np.asarray(budgets, dtype=np.int32)
     assert seq_lens.shape == (B,) and budgets.shape == (B,)
-    assert Hq % Hkv == 0 and np.all(seq_lens >= spec_k + 1)
+    # a context holds its own speculative tokens; `allow_short` lifts that for the tests of shorter ones
+    assert Hq % Hkv == 0 and np.all(seq_lens >= (1 if allow_short else spec_k + 1))
     n_q = spec_k + 1
     pages_per = (seq_lens.astype(np.int64) + P - 1) // P
     need = int(pages_per.sum())

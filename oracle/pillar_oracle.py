@@ -110,6 +110,12 @@ def verify_attn(w, requests=None, spec_lens=None):
     configurations).  Request b then has k_b+1 queries, the first k_b+1 of its
     k+1 query slots, query i at position L_b-(k_b+1)+i; its mean runs over
     (k_b+1)*G rows; out and lse of the unused slots stay zero.
+
+    A context shorter than its queries (L_b < k_b+1; the paper's contexts
+    always hold their own speculative tokens, so this is a reading for an
+    input outside its range): a query at a negative position sees no token,
+    its probabilities are all zero, its out row is zero, its lse is -inf, and
+    it still counts in R, so such a request's scores sum to less than one.
     """
     B, n_q_max, Hq, Hkv, D = w.B, w.n_q, w.Hq, w.Hkv, w.D
     G = Hq // Hkv
@@ -131,12 +137,14 @@ def verify_attn(w, requests=None, spec_lens=None):
             qg = q_all[b, :n_q, g * G:(g + 1) * G, :]     # [n_q, G, D]
             s = w.sm_scale * np.einsum("ihd,td->iht", qg, kg)      # [n_q, G, L]
             s = np.where(visible[:, None, :], s, -np.inf)
-            m = s.max(axis=-1, keepdims=True)
+            seen = visible.any(axis=-1)[:, None, None]    # False for a query whose position is negative
+            m = np.where(seen, s.max(axis=-1, keepdims=True), 0.0)
             e = np.exp(s - m)
             l = e.sum(axis=-1, keepdims=True)
-            p = e / l                                     # rows sum to one
+            p = e / np.where(seen, l, 1.0)                # rows sum to one (to zero when nothing is seen)
             out[b, :n_q, g * G:(g + 1) * G, :] = np.einsum("iht,td->ihd", p, vg)
-            lse[b, :n_q, g * G:(g + 1) * G] = (m + np.log(l))[..., 0]
+            with np.errstate(divide="ignore"):
+                lse[b, :n_q, g * G:(g + 1) * G] = (m + np.log(l))[..., 0]
             scores[b, g, :L] = p.sum(axis=(0, 1)) / R
     return out, lse, scores
 
@@ -207,7 +215,7 @@ def run_all(w):
 def window_indices(seq_lens, budgets, num_kv_heads, sink_tokens, max_budget=None):
     """Static 'attention sinks + recent window' selection: the sliding-window
     draft that the paper's related work and baselines use in place of a
-    dynamic pattern (Section 2, "Sparse self-speculation"; baselines of
+    dynamic pattern (Sections 1 and 3.3; the MagicDec-style baselines of
     Section 5).  Per request K' = min(budget, L, max_budget); the list holds
     the first min(sink_tokens, K') positions and the last K' minus that many,
     ascending, the same for every KV head, padded with -1; counts = K'.

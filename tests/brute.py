@@ -58,6 +58,10 @@ def verify(w):
                 last = L - n_q + i
                 for h in range(g * G, (g + 1) * G):
                     q = [_elem(x, w.q_dtype) for x in w.q[b][i][h]]
+                    if last < 0:                      # the query sees no token: nothing to normalise
+                        out[b][i][h] = [0.0] * w.D
+                        lse[b][i][h] = -math.inf
+                        continue
                     s = []
                     for t in range(last + 1):
                         d = 0.0

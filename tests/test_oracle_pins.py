@@ -85,6 +85,35 @@ def test_matches_pure_python_loops(seed, kw):
     np.testing.assert_allclose(r["draft_lse"], np.array(sl), rtol=1e-11, atol=1e-12)
 
 
+def test_context_shorter_than_its_queries():
+    """A request with fewer tokens than query rows (outside the paper's range: a reading).  Queries at
+    negative positions see nothing: zero output, lse -inf, no share of the statistic.  Pinned by the
+    pure-Python loops and by a closed form: with L = 1 only the last query sees token 0, with
+    probability one, so out = V[0], lse = its one logit and score[0] = G / R = 1 / (k+1)."""
+    w = tiny(16, B=2, spec_k=3, Hq=4, Hkv=2, D=8, seq_lens=[2, 1], budgets=[2, 1], allow_short=True)
+    out, lse, scores = oracle.verify_attn(w)
+    bo, bl, bs = brute.verify(w)
+    np.testing.assert_allclose(out, np.array(bo), rtol=1e-11, atol=1e-12)
+    np.testing.assert_array_equal(np.isneginf(lse), np.isneginf(np.array(bl)))
+    fin = np.isfinite(lse)
+    np.testing.assert_allclose(lse[fin], np.array(bl)[fin], rtol=1e-11, atol=1e-12)
+    for b in range(w.B):
+        L = int(w.seq_lens[b])
+        for g in range(w.Hkv):
+            np.testing.assert_allclose(scores[b, g, :L], np.array(bs[b][g]), rtol=1e-11, atol=1e-15)
+    # closed form, request 1 (L = 1, four query slots)
+    assert np.all(out[1, :3] == 0) and np.all(np.isneginf(lse[1, :3]))
+    k0, v0 = oracle.gather_request(w, 1)
+    for h in range(w.Hq):
+        g = h // w.G
+        np.testing.assert_allclose(out[1, 3, h], v0[0, g], rtol=1e-12)
+        q = oracle.decode_tensor(w.q, w.q_dtype)[1, 3, h]
+        assert abs(lse[1, 3, h] - w.sm_scale * float(q @ k0[0, g])) < 1e-12
+    np.testing.assert_allclose(scores[1, :, 0], 1.0 / w.n_q, rtol=1e-12)
+    # request 0 (L = 2): rows 2 and 3 are live, the sum of its scores is 2/4
+    np.testing.assert_allclose(scores[0, :, :2].sum(-1), 0.5, rtol=1e-12)
+
+
 def test_config1_matches_pure_python_loops_on_one_head_row():
     # config 1 itself, sampled: one (request, query, head) row by hand
     w = gen.make_workload(1)
