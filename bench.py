@@ -101,7 +101,7 @@ def main() -> int:
     import torch
     import gen
     import paper_2512_01278_amd as pa
-    from tests.harness import GpuRun
+    from paper_2512_01278_amd.runner import GpuRun
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     t_gen = time.perf_counter()

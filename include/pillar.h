@@ -87,8 +87,19 @@ typedef struct {
   const int32_t* block_table;  /* device [B][block_table_stride] */
   const int32_t* seq_lens;     /* device [B], 1 <= seq_lens[b] <= max_seq_len */
   int32_t max_seq_len;         /* host-known bound, <= block_table_stride*page_size */
-  int32_t reserved_;           /* set to 0 */
+  int32_t flags;               /* 0 or an OR of pillar_flag values; unknown bits: PILLAR_EINVAL */
 } pillar_kv_t;
+
+/* Per-call choices, carried in pillar_kv_t.flags.
+ *   PILLAR_FLAG_EXACT_SCORES     the verification reads K twice (once for the
+ *       log-sum-exp of every row, once more with V) and builds the score
+ *       statistic from fp32 probabilities, instead of reading K once and
+ *       rebuilding the statistic from 16-bit stashed exponentials.  Slower
+ *       (about 1.15x); scores then carry fp32 rounding only.
+ *   PILLAR_FLAG_GENERIC_KERNELS  every stage runs its plain vector-ALU kernel
+ *       even where a matrix-core kernel exists: a second implementation to
+ *       cross-check the fast one against.  Much slower. */
+typedef enum { PILLAR_FLAG_EXACT_SCORES = 1, PILLAR_FLAG_GENERIC_KERNELS = 2 } pillar_flag;
 
 /* Library version, major*10000 + minor*100 + patch. */
 int pillar_version(void);
@@ -110,11 +121,14 @@ size_t pillar_workspace_bytes(const pillar_kv_t* kv, int32_t spec_len_k, int32_t
  *          scores[b][g][t] = mean over the (k+1)*G rows of KV head g of the
  *          softmax probability that row assigns to token t (0 where the
  *          causal mask hides t).  Entries t >= seq_lens[b] are not written.
- *          score_stride >= max_seq_len.  With bf16 queries the relative
- *          error of a score is at most 4.9e-4 in the default mode (and a
- *          probability more than 2^63 times smaller than the largest one its
- *          row had met up to that token counts as 0), and that of fp32
- *          arithmetic with "verify_mode" 1 (see pillar_set_option). */
+ *          score_stride >= max_seq_len.  Accuracy on the matrix-core path
+ *          (bf16 queries): |error| <= 4.9e-4 * score + 2^-63, because every
+ *          row's exponential is kept to 11 significant bits and a probability
+ *          below 2^-63 (1.1e-19) counts as 0; with PILLAR_FLAG_EXACT_SCORES
+ *          the error is that of fp32 arithmetic.
+ *   Every request must hold its own speculative tokens: seq_lens[b] >= k+1.
+ *   A query row that sees no token at all (seq_lens[b] < k+1) gets out = 0 and
+ *   lse = -inf and adds nothing to the statistic. */
 int pillar_verify_attn(const pillar_kv_t* kv, const void* q, int32_t spec_len_k,
                        void* out, float* lse, float* scores, int64_t score_stride,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -140,8 +154,8 @@ int pillar_verify_select(const pillar_kv_t* kv, const void* q, int32_t spec_len_
  * With budgets / indices / counts non-NULL the critical tokens are selected as
  * by pillar_verify_select (all three NULL and max_budget 0: no selection).
  * Served by the matrix-core kernels only: bf16 queries, bf16 or fp8 KV,
- * head_dim 128, pages of >= 16 tokens, default "verify_mode"; anything else
- * returns PILLAR_EUNSUPPORTED. */
+ * head_dim 128, pages of >= 16 tokens, neither flag set; anything else returns
+ * PILLAR_EUNSUPPORTED.  seq_lens[b] >= spec_lens[b]+1 as above. */
 int pillar_verify_hetero(const pillar_kv_t* kv, const void* q, int32_t spec_len_max,
                          const int32_t* spec_lens, void* out, float* lse, float* scores,
                          int64_t score_stride, const int32_t* budgets, int32_t max_budget,
@@ -190,7 +204,8 @@ int pillar_append_kv(const pillar_kv_t* kv, const void* k_new, const void* v_new
  * page size 1 any token set is a list).
  *
  * pillar_window_indices: the static "attention sinks + recent window" pattern
- * of the sliding-window drafts the paper compares against (Section 2).  For
+ * of the sliding-window drafts the paper compares against (Sections 1, 3.3
+ * and 5.2).  For
  * request b, K' = min(budgets[b], seq_lens[b], max_budget); every head's list
  * holds the first min(sink_tokens, K') positions and the last K' minus that
  * many, ascending, padded with -1; counts[b] = K'.  All arrays on the device,
@@ -206,32 +221,6 @@ int pillar_window_indices(const int32_t* seq_lens, const int32_t* budgets, int32
 int pillar_extend_indices(int32_t* indices, int32_t* counts, const int32_t* first_new,
                           const int32_t* n_new, int32_t batch, int32_t num_kv_heads,
                           int32_t max_budget, void* hip_stream);
-
-/* Per-kernel timing for benchmarks.  pillar_profile_enable(1) makes every
- * later launch of this library be bracketed by HIP events on its stream;
- * pillar_profile_read synchronises the device, then fills up to `cap` entries
- * (host memory) with the kernels seen since the last pillar_profile_reset,
- * and returns how many there are.  Not meant for production paths: event
- * creation allocates. */
-typedef struct {
-  char   name[48];
-  int64_t launches;
-  double total_ms;
-} pillar_kernel_time;
-void pillar_profile_enable(int on);
-void pillar_profile_reset(void);
-int  pillar_profile_read(pillar_kernel_time* entries, int cap);
-
-/* Tuning knobs for benchmarking (process-wide, not thread-safe against
- * running calls).  Known names: "verify_waves" (wavefronts per compute unit
- * that the verification passes are divided among, 1..8), "verify_mode" (0: K
- * is read once and the score statistic is rebuilt from 16-bit stashed
- * exponentials, relative error up to 4.9e-4; 1: K is read twice and the
- * statistic is computed from fp32 probabilities) and "decode_rows" (rows of
- * the index list per wavefront of the draft kernel, a multiple of 32 up to
- * 4096).  A value of 0 restores the default.  Returns PILLAR_EINVAL for
- * an unknown name or a value outside the knob's range. */
-int pillar_set_option(const char* name, int64_t value);
 
 #ifdef __cplusplus
 }

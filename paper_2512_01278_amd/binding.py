@@ -3,7 +3,8 @@
 Every function here has the name and the argument order of its C entry point
 (include/pillar.h).  Tensors are torch tensors on the GPU, used as typed
 device pointers; nothing is computed in Python.  If the library has not been
-built, importing succeeds but every call raises: there is no fallback path.
+built, importing succeeds but every call raises: there is no fallback path.  The measurement helpers of
+include/pillar_bench.h are bound here too.
 """
 from __future__ import annotations
 
@@ -19,6 +20,7 @@ LIB_PATH = os.path.join(HERE, "libpillar.so")
 
 PILLAR_OK, PILLAR_EINVAL, PILLAR_EUNSUPPORTED, PILLAR_EWORKSPACE, PILLAR_EHIP = 0, -1, -2, -3, -4
 PILLAR_F32, PILLAR_BF16, PILLAR_FP8_E4M3 = 0, 1, 2
+PILLAR_FLAG_EXACT_SCORES, PILLAR_FLAG_GENERIC_KERNELS = 1, 2
 DTYPE_CODE = {"f32": PILLAR_F32, "bf16": PILLAR_BF16, "fp8_e4m3": PILLAR_FP8_E4M3}
 
 EXPORTS = ("pillar_version", "pillar_status_string", "pillar_workspace_bytes", "pillar_verify_attn",
@@ -37,7 +39,7 @@ class pillar_kv_t(C.Structure):
         ("k_scale", C.c_void_p), ("v_scale", C.c_void_p),
         ("num_pages", C.c_int32), ("block_table_stride", C.c_int32),
         ("block_table", C.c_void_p), ("seq_lens", C.c_void_p),
-        ("max_seq_len", C.c_int32), ("reserved_", C.c_int32),
+        ("max_seq_len", C.c_int32), ("flags", C.c_int32),
     ]
 
 
@@ -137,6 +139,7 @@ class KvCache:
     max_seq_len: int
     k_scale: Optional[torch.Tensor] = None
     v_scale: Optional[torch.Tensor] = None
+    flags: int = 0                 # OR of PILLAR_FLAG_*
 
     def c_struct(self) -> pillar_kv_t:
         kp = self.k_pool
@@ -159,7 +162,7 @@ class KvCache:
         s.block_table = self.block_table.data_ptr()
         s.seq_lens = self.seq_lens.data_ptr()
         s.max_seq_len = self.max_seq_len
-        s.reserved_ = 0
+        s.flags = self.flags
         return s
 
 

@@ -2,7 +2,7 @@
 // draft kernel (paper Section 4.2: with page size 1 any token set is a list).
 //
 //   window   the static "attention sinks + recent window" pattern of the
-//            sliding-window drafts the paper compares against (Section 2):
+//            sliding-window drafts the paper compares against (Sections 1, 3.3, 5.2):
 //            the first `sink_tokens` positions and the most recent ones;
 //   extend   tokens generated after the last verification have no score yet,
 //            but a draft step must see them: their positions are appended to

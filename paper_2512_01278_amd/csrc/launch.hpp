@@ -17,7 +17,7 @@ struct KernelTimer {
   ~KernelTimer();
   const char* name_;
   hipStream_t stream_;
-  hipEvent_t start_ = nullptr;
+  hipEvent_t start_ = nullptr, stop_ = nullptr;
 };
 
 // where a fused verification + selection leaves the critical tokens
@@ -39,6 +39,7 @@ struct VerifyArgs {
   int32_t q_dtype, kv_dtype;
   void* workspace;
   const SelectOut* select = nullptr;   // non-null: also select the Top-K of every (request, KV head)
+  bool exact_scores = false;           // PILLAR_FLAG_EXACT_SCORES: K read twice, fp32 probabilities
   const int32_t* spec_lens = nullptr;  // non-null: device [B], request b speculates spec_lens[b] <= n_q - 1 tokens
 };
 
@@ -84,13 +85,9 @@ bool decode_mfma_supported(const DecodeArgs& a);
 size_t decode_mfma_workspace(const KvView& kv, int max_budget);
 hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s);
 
-// true when the environment asks for the generic kernels everywhere
-bool force_generic();
-
 // process-wide tuning knobs (pillar_set_option); 0 = default
 struct Options {
   int verify_waves = 0;   // wavefronts per compute unit of the two verification passes
-  int verify_mode = 0;    // 0: K read once, 16-bit exponentials stashed; 1: K read twice, fp32 probabilities
   int decode_rows = 0;    // rows of the index list per wavefront of the draft kernel
 };
 Options& options();

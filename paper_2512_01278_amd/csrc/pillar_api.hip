@@ -3,7 +3,6 @@
 // synchronises (the optional profiler aside).
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -12,17 +11,22 @@
 
 #include "launch.hpp"
 #include "pillar.h"
+#include "pillar_bench.h"
 
 namespace pillar {
 
 // ---------------------------------------------------------------- profiler --
+// Event pairs come from a pool created by pillar_profile_enable: the entry points only record.
 namespace {
 struct Pending {
   const char* name;
   hipEvent_t start, stop;
 };
+constexpr size_t kEventPairs = 8192;
 std::mutex g_prof_mu;
 bool g_prof_on = false;
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_free;     // unused pairs
+bool g_pool_made = false;
 std::vector<Pending> g_pending;
 std::map<std::string, std::pair<int64_t, double>> g_totals;
 
@@ -34,8 +38,7 @@ void drain_locked() {
       e.first += 1;
       e.second += ms;
     }
-    (void)hipEventDestroy(p.start);
-    (void)hipEventDestroy(p.stop);
+    g_free.emplace_back(p.start, p.stop);
   }
   g_pending.clear();
 }
@@ -43,17 +46,19 @@ void drain_locked() {
 
 KernelTimer::KernelTimer(const char* name, hipStream_t stream) : name_(name), stream_(stream) {
   if (!g_prof_on) return;
-  if (hipEventCreate(&start_) != hipSuccess) { start_ = nullptr; return; }
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (g_free.empty()) return;                  // pool used up: this launch goes unrecorded
+  start_ = g_free.back().first;
+  stop_ = g_free.back().second;
+  g_free.pop_back();
   (void)hipEventRecord(start_, stream_);
 }
 
 KernelTimer::~KernelTimer() {
   if (!start_) return;
-  hipEvent_t stop;
-  if (hipEventCreate(&stop) != hipSuccess) { (void)hipEventDestroy(start_); return; }
-  (void)hipEventRecord(stop, stream_);
+  (void)hipEventRecord(stop_, stream_);
   std::lock_guard<std::mutex> lk(g_prof_mu);
-  g_pending.push_back({name_, start_, stop});
+  g_pending.push_back({name_, start_, stop_});
 }
 
 // -------------------------------------------------------------- validation --
@@ -79,6 +84,7 @@ int check_kv(const pillar_kv_t* kv) {
   if (kv->head_dim != 64 && kv->head_dim != 128) return PILLAR_EUNSUPPORTED;
   if (!pow2(kv->page_size) || kv->page_size > 256) return PILLAR_EUNSUPPORTED;
   if (kv->num_q_heads / kv->num_kv_heads > 16) return PILLAR_EUNSUPPORTED;
+  if (kv->flags & ~(PILLAR_FLAG_EXACT_SCORES | PILLAR_FLAG_GENERIC_KERNELS)) return PILLAR_EINVAL;
   return PILLAR_OK;
 }
 
@@ -134,13 +140,6 @@ Options& options() {
   return o;
 }
 
-bool force_generic() {
-  static const bool on = [] {
-    const char* e = std::getenv("PILLAR_FORCE_GENERIC");
-    return e && e[0] == '1';
-  }();
-  return on;
-}
 }  // namespace pillar
 
 using namespace pillar;
@@ -175,20 +174,22 @@ int verify_common(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, cons
   a.workspace = workspace;
   a.select = select;
   a.spec_lens = spec_lens;
+  a.exact_scores = (kv->flags & PILLAR_FLAG_EXACT_SCORES) != 0;
+  const bool generic = (kv->flags & PILLAR_FLAG_GENERIC_KERNELS) != 0;
   // per-request speculative lengths exist in the matrix-core single-pass kernels only
-  if (spec_lens && (force_generic() || !verify_range_supported(a))) return PILLAR_EUNSUPPORTED;
+  if (spec_lens && (generic || !verify_range_supported(a))) return PILLAR_EUNSUPPORTED;
   const size_t stage_ws = verify_workspace(a.kv, a.n_q);
   rc = check_workspace(workspace, workspace_bytes, stage_ws + (select ? scratch_scores_bytes(a.kv) : 0));
   if (rc != PILLAR_OK) return rc;
   const hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if (select && !(!force_generic() && verify_select_fused(a))) {
+  if (select && !(!generic && verify_select_fused(a))) {
     // two steps: the statistic goes through memory (the caller's buffer, or scratch behind the stage workspace)
     a.select = nullptr;
     if (!a.scores) {
       a.scores = reinterpret_cast<float*>(static_cast<char*>(workspace) + align_up(stage_ws, 256));
       a.score_stride = static_cast<int64_t>(scratch_score_stride(a.kv));
     }
-    const hipError_t e1 = (!force_generic() && verify_range_supported(a)) ? launch_verify_range(a, st) : launch_verify_generic(a, st);
+    const hipError_t e1 = (!generic && verify_range_supported(a)) ? launch_verify_range(a, st) : launch_verify_generic(a, st);
     if (e1 != hipSuccess) return PILLAR_EHIP;
     TopkArgs t;
     t.scores = a.scores;
@@ -204,7 +205,7 @@ int verify_common(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, cons
     return launch_topk(t, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
   }
   hipError_t e;
-  if (!force_generic() && verify_range_supported(a)) e = launch_verify_range(a, st);
+  if (!generic && verify_range_supported(a)) e = launch_verify_range(a, st);
   else e = launch_verify_generic(a, st);
   return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
 }
@@ -313,7 +314,7 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
   a.kv_dtype = kv->kv_dtype;
   a.workspace = workspace;
   const hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if (!force_generic() && decode_mfma_supported(a)) {
+  if (!(kv->flags & PILLAR_FLAG_GENERIC_KERNELS) && decode_mfma_supported(a)) {
     rc = check_workspace(workspace, workspace_bytes, decode_mfma_workspace(a.kv, max_budget));
     if (rc != PILLAR_OK) return rc;
     return launch_decode_mfma(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
@@ -360,9 +361,6 @@ int pillar_set_option(const char* name, int64_t value) {
   if (k == "verify_waves") {
     if (value > 8) return PILLAR_EINVAL;
     o.verify_waves = static_cast<int>(value);
-  } else if (k == "verify_mode") {
-    if (value > 1) return PILLAR_EINVAL;
-    o.verify_mode = static_cast<int>(value);
   } else if (k == "decode_rows") {
     if (value % 32 != 0 || value > 4096) return PILLAR_EINVAL;
     o.decode_rows = static_cast<int>(value);
@@ -375,6 +373,15 @@ int pillar_set_option(const char* name, int64_t value) {
 
 void pillar_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (on && !g_pool_made) {
+    g_pool_made = true;
+    for (size_t i = 0; i < kEventPairs; ++i) {
+      hipEvent_t a = nullptr, b = nullptr;
+      if (hipEventCreate(&a) != hipSuccess) break;
+      if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); break; }
+      g_free.emplace_back(a, b);
+    }
+  }
   g_prof_on = on != 0;
 }
 

@@ -1,6 +1,5 @@
-// Critical-token selection: Top-K of the verification scores per
-// (request, KV head) -- paper Section 4.1, "the sparsity pattern can be
-// directly identified by ... applying Top-K on the dumped attention scores".
+// Critical-token selection: Top-K of the averaged verification scores per
+// (request, KV head) -- paper Section 4.1.
 //
 // Exact radix select.  A float's bit pattern, mapped to an unsigned key whose
 // integer order is the float order, is resolved 8 bits at a time from the top:

@@ -141,11 +141,12 @@ __global__ __launch_bounds__(kThreads) void verify_merge_generic(KvView kv, int 
     }
     const int i = r / G, hg = r - i * G;
     const int64_t row = (static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg;
-    Storage<QDT>::store(out, row * D + d, o / l);
+    const bool live = l > 0.f;                 // false for a row that sees no token at all: zeros, lse = -inf
+    Storage<QDT>::store(out, row * D + d, live ? o / l : 0.f);
     if (d == 0) {
       const float v = m + __logf(l);
-      ws.lse[(static_cast<int64_t>(b) * kv.num_kv_heads + g) * R + r] = v;
-      if (lse_out) lse_out[row] = v;
+      ws.lse[(static_cast<int64_t>(b) * kv.num_kv_heads + g) * R + r] = live ? v : INFINITY;   // +inf: no weight in the statistic
+      if (lse_out) lse_out[row] = live ? v : -INFINITY;
     }
   }
 }

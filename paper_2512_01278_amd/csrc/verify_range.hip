@@ -18,7 +18,7 @@
 //                     plus Top-K from on-chip scores (verify_select_finish)
 //   merge             O = sum over segments of exp2(m_seg - lse) O_seg
 //
-// Variant with fp32 probabilities, K read twice (option verify_mode 1):
+// Variant with fp32 probabilities, K read twice (PILLAR_FLAG_EXACT_SCORES):
 //   pass 1 (K only)   running (max, sum) per row -> (m, l) per row and segment
 //   combine           as above
 //   pass 2 (K and V)  p = exp2(s - lse) is the exact probability: the score is
@@ -423,13 +423,15 @@ __global__ __launch_bounds__(256) void verify_lse_combine_range(KvView kv, int n
     l = l * fast_exp2(m - mu) + lc * fast_exp2(mc - mu);
     m = mn;
   }
-  // rows beyond the request's R get +inf so that their probabilities vanish where the log-sum-exp is applied
+  // rows beyond the request's R, and rows that see no token at all (a context shorter than the request's
+  // queries), get +inf so that their probabilities vanish where the log-sum-exp is applied
   const int Rb = queries_of(ws, b, n_q) * G;
-  const float v = row < Rb ? m + log2f(l) : INFINITY;
+  const bool live = row < Rb && l > 0.f;
+  const float v = live ? m + log2f(l) : INFINITY;
   ws.lse2[idx] = v;
   if (lse_out && row < Rb) {
     const int i = row / G, hg = row - i * G;
-    lse_out[(static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg] = v * kLn2;
+    lse_out[(static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg] = live ? v * kLn2 : -INFINITY;
   }
 }
 
@@ -667,7 +669,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, con
       }
       if (r >= Rb) continue;               // rows of query slots the request does not use are left alone
       if (whole) {
-        const float inv = 1.0f / l;
+        const float inv = l > 0.f ? 1.0f / l : 0.f;       // a row that sees no token: zeros
         const int i = r / G, hg = r - i * G;
         uint16_t* dst = out + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim;
 #pragma unroll
@@ -935,7 +937,7 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
       }
       if (r >= Rb) continue;               // rows of query slots the request does not use are left alone
       if (whole) {
-        const float inv = 1.0f / l;
+        const float inv = l > 0.f ? 1.0f / l : 0.f;       // a row that sees no token: zeros
         const int i = r / G, hg = r - i * G;
         uint16_t* dst = out + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim;
 #pragma unroll
@@ -1361,7 +1363,7 @@ hipError_t run(const VerifyArgs& a, hipStream_t st) {
     KernelTimer t("verify_range_plan", st);
     hipLaunchKernelGGL(range_plan, dim3(1), dim3(1024), 0, st, kv, ws);
   }
-  if (options().verify_mode == 0 || !a.scores || a.select) {
+  if (!a.exact_scores || !(a.scores || a.select)) {
     {
       KernelTimer t("verify_flash_range", st);
       const bool stash = a.scores || a.select;
@@ -1440,7 +1442,7 @@ bool verify_range_supported(const VerifyArgs& a) {
   if (kv.head_dim != kHeadDim || kv.page_size < 16) return false;
   if (row_blocks(kv, a.n_q) > 4) return false;
   if (!(kv.sm_scale > 0.f)) return false;       // the kernels take row maxima before scaling
-  if (a.spec_lens && options().verify_mode != 0) return false;   // per-request lengths: single-pass kernels only
+  if (a.spec_lens && a.exact_scores) return false;   // per-request lengths: single-pass kernels only
   const int64_t align = a.kv_dtype == PILLAR_BF16 ? 8 : 16;      // elements per 16 bytes
   if (kv.stride_page % align || kv.stride_head % align || kv.stride_slot % align) return false;
   if ((reinterpret_cast<uintptr_t>(kv.k_pool) | reinterpret_cast<uintptr_t>(kv.v_pool) | reinterpret_cast<uintptr_t>(a.q) |
@@ -1456,7 +1458,7 @@ bool verify_range_supported(const VerifyArgs& a) {
 bool verify_select_fused(const VerifyArgs& a) {
   // rows of more than 16 K tokens would need 128 KB of LDS per workgroup, one workgroup per compute unit:
   // measured slower than the two kernels (config 5: 167 against 139 us), so those take the two steps
-  return a.select && verify_range_supported(a) && options().verify_mode == 0 && a.kv.max_seq_len <= kSelectThreads * 16;
+  return a.select && verify_range_supported(a) && !a.exact_scores && a.kv.max_seq_len <= kSelectThreads * 16;
 }
 
 size_t verify_range_workspace(const KvView& kv, int n_q) {

@@ -7,6 +7,7 @@ import torch
 
 import oracle
 import paper_2512_01278_amd as pa
+from paper_2512_01278_amd.runner import GpuRun
 
 # Tolerances (the bf16 / fp8 ones are the stated targets of this build; the
 # fp32 ones follow from fp32 accumulation over <= 32768 terms: a few 1e-6
@@ -18,66 +19,18 @@ OUT_TOL = {  # kv dtype -> (max abs, rel L2)
 }
 SCORE_REL = 1e-3
 SCORE_FLOOR = 1e-20
+# The default matrix-core verification keeps every row's exponential as a 16-bit value whose exponent
+# reaches down to 2^-63 of the row's running maximum; a smaller probability (all of them are below 2^-63
+# themselves) is dropped.  Where a test drives probabilities that low on purpose it grants this much
+# absolute slack on top of the relative bound (reading R19 of the design notes); everywhere else the
+# bound is the relative one alone.
+SCORE_FLUSH = 2.0 ** -63
 LSE_ABS = 2e-4
 TIE_BAND = 1e-3
-
-_TORCH = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 
 def to_f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().to(torch.float64).cpu().numpy()
-
-
-class GpuRun:
-    """Uploads a workload once and runs stages on it."""
-
-    def __init__(self, w, device="cuda:0"):
-        self.w = w
-        self.dev = torch.device(device)
-        self.dw = pa.upload_workload(w, device)
-        kv = self.dw.kv
-        B, Hq, Hkv, D, n_q = w.B, w.Hq, w.Hkv, w.D, w.n_q
-        self.max_budget = max(1, int(w.budgets.max()))
-        nbytes = pa.pillar_workspace_bytes(kv, w.spec_k, self.max_budget)
-        assert nbytes > 0
-        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
-        qd = _TORCH[w.q_dtype]
-        self.out = torch.full((B, n_q, Hq, D), float("nan"), dtype=qd, device=self.dev)
-        self.lse = torch.full((B, n_q, Hq), float("nan"), dtype=torch.float32, device=self.dev)
-        self.score_stride = (w.max_seq_len + 63) // 64 * 64
-        self.scores = torch.full((B, Hkv, self.score_stride), float("nan"), dtype=torch.float32, device=self.dev)
-        self.indices = torch.full((B, Hkv, self.max_budget), -7, dtype=torch.int32, device=self.dev)
-        self.counts = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
-        self.d_out = torch.full((B, Hq, D), float("nan"), dtype=qd, device=self.dev)
-        self.d_lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device=self.dev)
-
-    def verify(self, with_scores=True, with_lse=True):
-        pa.pillar_verify_attn(self.dw.kv, self.dw.q, self.w.spec_k, self.out,
-                              self.lse if with_lse else None, self.scores if with_scores else None,
-                              self.workspace)
-
-    def verify_select(self, with_scores=True, with_lse=True):
-        pa.pillar_verify_select(self.dw.kv, self.dw.q, self.w.spec_k, self.out, self.lse if with_lse else None,
-                                self.scores if with_scores else None, self.dw.budgets, self.max_budget,
-                                self.indices, self.counts, self.workspace)
-
-    def topk(self, scores=None):
-        pa.pillar_select_topk(self.scores if scores is None else scores, self.dw.kv.seq_lens, self.dw.budgets,
-                              self.w.max_seq_len, self.max_budget, self.indices, self.counts, self.workspace)
-
-    def decode(self, indices=None, counts=None):
-        pa.pillar_sparse_decode(self.dw.kv, self.dw.q_draft, self.indices if indices is None else indices,
-                                self.counts if counts is None else counts, self.max_budget, self.d_out,
-                                self.d_lse, self.workspace)
-
-    def run_all(self, fused_select=False):
-        if fused_select:
-            self.verify_select()
-        else:
-            self.verify()
-            self.topk()
-        self.decode()
-        torch.cuda.synchronize()
 
 
 def check_out(got: np.ndarray, want: np.ndarray, kv_dtype: str, what: str):
@@ -90,13 +43,13 @@ def check_out(got: np.ndarray, want: np.ndarray, kv_dtype: str, what: str):
     return err, rel
 
 
-def check_scores(got: np.ndarray, want: np.ndarray, seq_lens, requests, what: str):
+def check_scores(got: np.ndarray, want: np.ndarray, seq_lens, requests, what: str, abs_slack: float = 0.0):
     worst = 0.0
     for b in requests:
         L = int(seq_lens[b])
         g_, w_ = got[b, :, :L], want[b, :, :L]
         assert not np.isnan(g_).any(), f"{what}: NaN score, request {b}"
-        rel = np.abs(g_ - w_) / np.maximum(w_, SCORE_FLOOR)
+        rel = np.maximum(np.abs(g_ - w_) - abs_slack, 0.0) / np.maximum(w_, SCORE_FLOOR)
         worst = max(worst, float(rel.max()))
         assert rel.max() <= SCORE_REL, f"{what}: score rel error {rel.max():.3e} at request {b}"
     return worst

@@ -33,9 +33,11 @@ def good_kv(**kw):
 
 
 def test_header_functions_are_all_exported(lib):
-    text = open(os.path.join(ROOT, "include", "pillar.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = set(re.findall(r"\b(pillar_[a-z_]+)\s*\(", text))
+    names = set()
+    for header in ("pillar.h", "pillar_bench.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(pillar_[a-z_]+)\s*\(", text))
     assert names == set(pb.EXPORTS), names ^ set(pb.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
@@ -75,6 +77,7 @@ def test_workspace_query(lib):
     (dict(head_dim=96, stride_slot=128), pb.PILLAR_EUNSUPPORTED), (dict(page_size=24), pb.PILLAR_EUNSUPPORTED),
     (dict(q_dtype=pb.PILLAR_FP8_E4M3), pb.PILLAR_EUNSUPPORTED), (dict(kv_dtype=7), pb.PILLAR_EUNSUPPORTED),
     (dict(num_q_heads=8 * 32), pb.PILLAR_EUNSUPPORTED),
+    (dict(flags=4), pb.PILLAR_EINVAL), (dict(flags=-1), pb.PILLAR_EINVAL),
 ])
 def test_bad_cache_descriptions_are_rejected(lib, kw, code):
     s = good_kv(**kw)
@@ -113,6 +116,8 @@ def test_bad_call_arguments_are_rejected(lib):
     assert vh(budgets=FAKE) == pb.PILLAR_EINVAL                      # selection wanted, but not all of its arguments
     assert vh(budgets=FAKE, idx=FAKE, cnt=FAKE, mb=0) == pb.PILLAR_EINVAL
     assert vh(kv=good_kv(q_dtype=pb.PILLAR_F32, kv_dtype=pb.PILLAR_F32)) == pb.PILLAR_EUNSUPPORTED   # generic kernels only
+    assert vh(kv=good_kv(flags=pb.PILLAR_FLAG_EXACT_SCORES)) == pb.PILLAR_EUNSUPPORTED
+    assert vh(kv=good_kv(flags=pb.PILLAR_FLAG_GENERIC_KERNELS)) == pb.PILLAR_EUNSUPPORTED
     assert lib.pillar_append_kv(C.byref(s), None, FAKE, 3, None) == pb.PILLAR_EINVAL
     assert lib.pillar_append_kv(C.byref(s), FAKE, FAKE, 0, None) == pb.PILLAR_EINVAL
     assert lib.pillar_append_kv(C.byref(good_kv(kv_dtype=pb.PILLAR_FP8_E4M3, k_scale=FAKE, v_scale=FAKE)), FAKE, FAKE, 3, None) \
@@ -130,11 +135,10 @@ def test_bad_call_arguments_are_rejected(lib):
 def test_option_names_and_ranges(lib):
     lib.pillar_set_option.restype = C.c_int
     lib.pillar_set_option.argtypes = [C.c_char_p, C.c_int64]
-    ok = [(b"verify_waves", 4), (b"verify_waves", 0), (b"verify_mode", 1), (b"verify_mode", 0),
-          (b"decode_rows", 64), (b"decode_rows", 0)]
+    ok = [(b"verify_waves", 4), (b"verify_waves", 0), (b"decode_rows", 64), (b"decode_rows", 0)]
     for name, value in ok:
         assert lib.pillar_set_option(name, value) == 0, (name, value)
-    bad = [(b"verify_waves", 9), (b"verify_mode", 2), (b"decode_rows", 48), (b"decode_rows", 8192),
+    bad = [(b"verify_waves", 9), (b"verify_mode", 1), (b"decode_rows", 48), (b"decode_rows", 8192),
            (b"verify_waves", -1), (b"no_such_knob", 1), (None, 1)]
     for name, value in bad:
         assert lib.pillar_set_option(name, value) == -1, (name, value)
