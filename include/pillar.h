@@ -54,7 +54,8 @@ typedef enum {
   PILLAR_EINVAL = -1,        /* NULL pointer, non-positive size, inconsistent shapes */
   PILLAR_EUNSUPPORTED = -2,  /* well-formed but outside the supported shapes/dtypes */
   PILLAR_EWORKSPACE = -3,    /* workspace NULL, misaligned or too small */
-  PILLAR_EHIP = -4           /* the HIP runtime refused a launch */
+  PILLAR_EHIP = -4,          /* the HIP runtime refused a launch */
+  PILLAR_ETOOLARGE = -5      /* pillar_sparse_decode_static only: needs more than its fixed scratch */
 } pillar_status;
 
 typedef enum { PILLAR_F32 = 0, PILLAR_BF16 = 1, PILLAR_FP8_E4M3 = 2 } pillar_dtype;
@@ -189,6 +190,23 @@ int pillar_select_topk(const float* scores, int64_t score_stride, const int32_t*
 int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* indices,
                          const int32_t* counts, int32_t max_budget, void* out, float* lse,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* pillar_sparse_decode for callers that can hand over no workspace and must
+ * not cause an allocation: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * result bits as pillar_sparse_decode, but the partial results of index lists
+ * that are split over several wavefronts go to a 32 MiB array inside the
+ * library (one copy per GPU, held until the process ends) instead of a
+ * workspace.  A shape whose pillar_sparse_decode would need more than those
+ * 32 MiB (batch * Hkv * splits * G rows of 128 floats; about 60000 (request, KV
+ * head, split) units at G = 4) returns PILLAR_ETOOLARGE and launches nothing.
+ * Calls no allocator.  All calls on one GPU share the one array: two such
+ * calls that overlap in time on the same GPU (different streams) race; order
+ * them.  The first call on a device looks the array's address up; make it
+ * outside any stream capture. */
+int pillar_sparse_decode_static(const pillar_kv_t* kv, const void* q, const int32_t* indices,
+                                const int32_t* counts, int32_t max_budget, void* out, float* lse,
+                                void* hip_stream);
 
 /* The write that precedes a verification: the K/V rows of the n_new newest
  * tokens of every request go into their pages (append, then attend:

@@ -18,13 +18,13 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libpillar.so")
 
-PILLAR_OK, PILLAR_EINVAL, PILLAR_EUNSUPPORTED, PILLAR_EWORKSPACE, PILLAR_EHIP = 0, -1, -2, -3, -4
+PILLAR_OK, PILLAR_EINVAL, PILLAR_EUNSUPPORTED, PILLAR_EWORKSPACE, PILLAR_EHIP, PILLAR_ETOOLARGE = 0, -1, -2, -3, -4, -5
 PILLAR_F32, PILLAR_BF16, PILLAR_FP8_E4M3 = 0, 1, 2
 PILLAR_FLAG_EXACT_SCORES, PILLAR_FLAG_GENERIC_KERNELS = 1, 2
 DTYPE_CODE = {"f32": PILLAR_F32, "bf16": PILLAR_BF16, "fp8_e4m3": PILLAR_FP8_E4M3}
 
 EXPORTS = ("pillar_version", "pillar_status_string", "pillar_workspace_bytes", "pillar_verify_attn",
-           "pillar_verify_select", "pillar_verify_hetero", "pillar_select_topk", "pillar_sparse_decode", "pillar_window_indices",
+           "pillar_verify_select", "pillar_verify_hetero", "pillar_select_topk", "pillar_sparse_decode", "pillar_sparse_decode_static", "pillar_window_indices",
            "pillar_extend_indices", "pillar_append_kv", "pillar_profile_enable", "pillar_profile_reset",
            "pillar_profile_read", "pillar_set_option")
 
@@ -88,6 +88,9 @@ def load() -> C.CDLL:
     lib.pillar_sparse_decode.restype = C.c_int
     lib.pillar_sparse_decode.argtypes = [C.POINTER(pillar_kv_t), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.pillar_sparse_decode_static.restype = C.c_int
+    lib.pillar_sparse_decode_static.argtypes = [C.POINTER(pillar_kv_t), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                                C.c_void_p, C.c_void_p, C.c_void_p]
     lib.pillar_append_kv.restype = C.c_int
     lib.pillar_append_kv.argtypes = [C.POINTER(pillar_kv_t), C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
     lib.pillar_window_indices.restype = C.c_int
@@ -231,6 +234,14 @@ def pillar_sparse_decode(kv: KvCache, q: torch.Tensor, indices: torch.Tensor, co
     rc = load().pillar_sparse_decode(C.byref(s), q.data_ptr(), indices.data_ptr(), counts.data_ptr(), max_budget,
                                      out.data_ptr(), _ptr(lse), _ptr(workspace), wsz, _stream(stream))
     _check(rc, "pillar_sparse_decode")
+
+
+def pillar_sparse_decode_static(kv: KvCache, q: torch.Tensor, indices: torch.Tensor, counts: torch.Tensor,
+                                max_budget: int, out: torch.Tensor, lse: Optional[torch.Tensor], stream=None) -> None:
+    s = kv.c_struct()
+    rc = load().pillar_sparse_decode_static(C.byref(s), q.data_ptr(), indices.data_ptr(), counts.data_ptr(), max_budget,
+                                            out.data_ptr(), _ptr(lse), _stream(stream))
+    _check(rc, "pillar_sparse_decode_static")
 
 
 def pillar_append_kv(kv: KvCache, k_new: torch.Tensor, v_new: torch.Tensor, stream=None) -> None:

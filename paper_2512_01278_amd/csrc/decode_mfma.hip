@@ -17,6 +17,7 @@
 // fit one split are finished in the kernel; longer lists leave (max, sum, O)
 // partials that a second small kernel combines.
 #include <algorithm>
+#include <mutex>
 
 #include "launch.hpp"
 #include "mfma_tile.hpp"
@@ -288,6 +289,45 @@ bool decode_mfma_supported(const DecodeArgs& a) {
        reinterpret_cast<uintptr_t>(a.out)) & 15u)
     return false;
   return true;
+}
+
+// ---- scratch of the entry point that takes no workspace -------------------------------------
+// Split partials of pillar_sparse_decode_static live in this array instead of a caller's buffer.
+// Every GPU the library runs on holds its own copy at its own address until the process ends; the
+// array's name is only a host-side handle, the address the kernels get comes from the runtime.
+constexpr size_t kStaticScratchBytes = size_t{32} << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up once per device)
+hipError_t static_scratch(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+}  // namespace
+
+size_t decode_static_scratch_bytes() { return kStaticScratchBytes; }
+
+hipError_t launch_decode_mfma_static(const DecodeArgs& a, hipStream_t s) {
+  DecodeArgs b = a;
+  const hipError_t e = static_scratch(&b.workspace);
+  if (e != hipSuccess) return e;
+  return launch_decode_mfma(b, s);
 }
 
 size_t decode_mfma_workspace(const KvView& kv, int max_budget) {

@@ -84,6 +84,8 @@ bool verify_select_fused(const VerifyArgs& a);          // a.select can be serve
 bool decode_mfma_supported(const DecodeArgs& a);
 size_t decode_mfma_workspace(const KvView& kv, int max_budget);
 hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s);
+size_t decode_static_scratch_bytes();                     // size of the library's own scratch array
+hipError_t launch_decode_mfma_static(const DecodeArgs& a, hipStream_t s);   // same kernels, partials in that array
 
 // process-wide tuning knobs (pillar_set_option); 0 = default
 struct Options {

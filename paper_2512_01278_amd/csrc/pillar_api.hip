@@ -223,6 +223,7 @@ const char* pillar_status_string(int status) {
     case PILLAR_EUNSUPPORTED: return "shape or dtype outside the supported set";
     case PILLAR_EWORKSPACE: return "workspace null, not 256-byte aligned, or too small";
     case PILLAR_EHIP: return "HIP runtime error at launch";
+    case PILLAR_ETOOLARGE: return "the problem needs more scratch than the library's own 32 MiB array holds: use the entry point that takes a workspace";
     default: return "unknown status";
   }
 }
@@ -320,6 +321,31 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
     return launch_decode_mfma(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
   }
   return launch_decode_generic(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+}
+
+int pillar_sparse_decode_static(const pillar_kv_t* kv, const void* q, const int32_t* indices, const int32_t* counts,
+                                int32_t max_budget, void* out, float* lse, void* hip_stream) {
+  int rc = check_kv(kv);
+  if (rc != PILLAR_OK) return rc;
+  if (!q || !indices || !counts || !out) return PILLAR_EINVAL;
+  if (max_budget < 1) return PILLAR_EINVAL;
+  DecodeArgs a;
+  a.kv = make_view(kv);
+  a.q = q;
+  a.indices = indices;
+  a.counts = counts;
+  a.max_budget = max_budget;
+  a.out = out;
+  a.lse = lse;
+  a.q_dtype = kv->q_dtype;
+  a.kv_dtype = kv->kv_dtype;
+  a.workspace = nullptr;
+  const hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (!(kv->flags & PILLAR_FLAG_GENERIC_KERNELS) && decode_mfma_supported(a)) {
+    if (decode_mfma_workspace(a.kv, max_budget) > decode_static_scratch_bytes()) return PILLAR_ETOOLARGE;
+    return launch_decode_mfma_static(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+  }
+  return launch_decode_generic(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;     // needs no scratch at all
 }
 
 int pillar_append_kv(const pillar_kv_t* kv, const void* k_new, const void* v_new, int32_t n_new, void* hip_stream) {

@@ -51,8 +51,8 @@ def test_struct_layout_matches_the_header():
 
 def test_version_and_status_strings(lib):
     assert lib.pillar_version() >= 100
-    seen = {lib.pillar_status_string(c) for c in (0, -1, -2, -3, -4)}
-    assert len(seen) == 5 and b"unknown" in lib.pillar_status_string(-99)
+    seen = {lib.pillar_status_string(c) for c in (0, -1, -2, -3, -4, -5)}
+    assert len(seen) == 6 and b"unknown" in lib.pillar_status_string(-99)
 
 
 def verify(lib, s, q=FAKE, k=4, out=FAKE, scores=FAKE, stride=1024, ws=FAKE, wsz=1 << 40):
@@ -130,6 +130,15 @@ def test_bad_call_arguments_are_rejected(lib):
                                               k.get("mb", 256), k.get("out", FAKE), None, FAKE, 1 << 40, None)
     assert sd(q=None) == pb.PILLAR_EINVAL and sd(idx=None) == pb.PILLAR_EINVAL
     assert sd(cnt=None) == pb.PILLAR_EINVAL and sd(out=None) == pb.PILLAR_EINVAL and sd(mb=0) == pb.PILLAR_EINVAL
+
+
+def test_static_decode_rejects_what_its_scratch_cannot_hold(lib):
+    sds = lambda s, mb=256, q=FAKE: lib.pillar_sparse_decode_static(C.byref(s), q, FAKE, FAKE, mb, FAKE, None, None)
+    assert sds(good_kv(), q=None) == pb.PILLAR_EINVAL and sds(good_kv(), mb=0) == pb.PILLAR_EINVAL
+    assert sds(good_kv(batch=0)) == pb.PILLAR_EINVAL
+    # 2048 requests x 8 heads x 8 splits x 4 rows x 512 B of partial results = 268 MB: beyond the 32 MiB array
+    assert sds(good_kv(batch=2048, max_seq_len=1024), mb=1024) == pb.PILLAR_ETOOLARGE
+    assert b"32 MiB" in lib.pillar_status_string(pb.PILLAR_ETOOLARGE)
 
 
 def test_option_names_and_ranges(lib):
