@@ -123,9 +123,9 @@ size_t pillar_workspace_bytes(const pillar_kv_t* kv, int32_t spec_len_k, int32_t
  *          softmax probability that row assigns to token t (0 where the
  *          causal mask hides t).  Entries t >= seq_lens[b] are not written.
  *          score_stride >= max_seq_len.  Accuracy on the matrix-core path
- *          (bf16 queries): |error| <= 4.9e-4 * score + 2^-63, because every
+ *          (bf16 queries): |error| <= 4.9e-4 * score + 2^-62, because every
  *          row's exponential is kept to 11 significant bits and a probability
- *          below 2^-63 (1.1e-19) counts as 0; with PILLAR_FLAG_EXACT_SCORES
+ *          below 2^-62 (2.2e-19) counts as 0; with PILLAR_FLAG_EXACT_SCORES
  *          the error is that of fp32 arithmetic.
  *   Every request must hold its own speculative tokens: seq_lens[b] >= k+1.
  *   A query row that sees no token at all (seq_lens[b] < k+1) gets out = 0 and

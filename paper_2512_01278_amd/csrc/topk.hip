@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void topk_radix(TopkArgs a) {
 // consecutive keys, so the row is read once and the ordered emission is one scan (topk_core.hpp).
 template <int KPT>
 __global__ __launch_bounds__(kThreads) void topk_select(TopkArgs a) {
-  __shared__ SelectLds lds;
+  __shared__ SelectLds<kThreads, 1> lds;
   const int b = blockIdx.y, g = blockIdx.x;
   const int L = a.seq_lens[b];
   const int K = max(0, min(min(a.budgets[b], L), a.max_budget));
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(kThreads) void topk_select(TopkArgs a) {
 
   // thread t holds positions t*KPT .. t*KPT+KPT-1
   const int t0 = threadIdx.x * KPT;
-  uint32_t key[KPT];
+  uint32_t key[1][KPT];
   if ((a.score_stride & 3) == 0 && (reinterpret_cast<uintptr_t>(a.scores) & 15u) == 0) {
 #pragma unroll
     for (int j = 0; j < KPT; j += 4) {
@@ -156,13 +156,13 @@ __global__ __launch_bounds__(kThreads) void topk_select(TopkArgs a) {
         if (t0 + j + 1 < L) v.y = row[t0 + j + 1];
         if (t0 + j + 2 < L) v.z = row[t0 + j + 2];
       }
-      key[j] = order_key(v.x); key[j + 1] = order_key(v.y); key[j + 2] = order_key(v.z); key[j + 3] = order_key(v.w);
+      key[0][j] = order_key(v.x); key[0][j + 1] = order_key(v.y); key[0][j + 2] = order_key(v.z); key[0][j + 3] = order_key(v.w);
     }
   } else {
 #pragma unroll
-    for (int j = 0; j < KPT; ++j) key[j] = order_key(t0 + j < L ? row[t0 + j] : 0.f);
+    for (int j = 0; j < KPT; ++j) key[0][j] = order_key(t0 + j < L ? row[t0 + j] : 0.f);
   }
-  select_topk_in_registers<KPT>(key, t0, L, K, out, lds);
+  select_topk_in_registers<kThreads, KPT, 1>(key, L, K, out, lds);
 }
 
 }  // namespace

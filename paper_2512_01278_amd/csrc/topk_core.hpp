@@ -1,6 +1,6 @@
-// Exact selection of the K largest of up to kSelectThreads * KPT keys held in registers by one
-// 1024-thread workgroup (paper Section 4.1: Top-K on the averaged scores).  Shared by the stand-alone
-// Top-K kernel and by the verification finish kernel that selects straight from on-chip scores.
+// Exact selection of the K largest keys held in registers by one workgroup (paper Section 4.1: Top-K on
+// the averaged scores).  Shared by the stand-alone Top-K kernel and by the verification finish kernel,
+// which selects straight from on-chip scores.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -10,9 +10,6 @@
 
 namespace pillar {
 namespace {
-
-constexpr int kSelectThreads = 1024;
-constexpr int kSelectWaves = kSelectThreads / kWave;
 
 // float -> unsigned key whose integer order is the float order
 __device__ __forceinline__ uint32_t order_key(float f) {
@@ -34,26 +31,29 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v) {
   return static_cast<uint32_t>(x);
 }
 
-// LDS the selection needs (one instance per workgroup).
-struct SelectLds {
+// LDS the selection needs (one instance per workgroup of THREADS threads holding CH chunks of keys).
+template <int THREADS, int CH> struct SelectLds {
   uint32_t hist[4096];
-  uint32_t wave_sum[2][kSelectWaves];
-  uint32_t prefix, remaining;
+  uint32_t wave_sum[2][CH][THREADS / kWave];
+  uint32_t prefix[3], remaining[3];        // one slot per pass: no barrier between reading one and writing the next
 };
 
-// Thread t holds the keys of positions t*KPT .. t*KPT+KPT-1 (`t0` = t*KPT); positions >= L are ignored.
-// Writes the K selected positions in ascending order to out[0..K).  Three histogram passes of 12, 12 and
-// 8 bits find the K-th largest key: the wide first digit (sign, exponent and three mantissa bits) spreads
-// attention scores, which share a few exponents, over many more bins than an 8-bit digit does, and that is
-// what keeps the LDS histogram increments from serialising.  Every thread of the workgroup must call this.
-template <int KPT>
-__device__ __forceinline__ void select_topk_in_registers(const uint32_t (&key)[KPT], int t0, int L, int K, int32_t* out,
-                                                         SelectLds& lds) {
+// The workgroup holds CH * THREADS * KPC keys: key[c][j] of thread t belongs to position
+// c * (THREADS * KPC) + t * KPC + j; positions >= L are ignored.  Writes the K selected positions in
+// ascending order to out[0..K).  Three histogram passes of 12, 12 and 8 bits find the K-th largest key:
+// the wide first digit (sign, exponent and three mantissa bits) spreads attention scores, which share a
+// few exponents, over many more bins than an 8-bit digit does, and that is what keeps the LDS histogram
+// increments from serialising.  Equal keys go to the lower position.  Every thread of the workgroup must
+// call this.
+template <int THREADS, int KPC, int CH>
+__device__ __forceinline__ void select_topk_in_registers(const uint32_t (&key)[CH][KPC], int L, int K, int32_t* out,
+                                                         SelectLds<THREADS, CH>& lds) {
+  constexpr int kWaves = THREADS / kWave;
+  constexpr int kChunk = THREADS * KPC;
+  static_assert(4096 % THREADS == 0 && THREADS >= 256, "bins are dealt out evenly");
   uint32_t* hist = lds.hist;
-  uint32_t (*wave_sum)[kSelectWaves] = lds.wave_sum;
-  uint32_t& sh_prefix = lds.prefix;
-  uint32_t& sh_remaining = lds.remaining;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int t0 = static_cast<int>(threadIdx.x) * KPC;
   uint32_t prefix = 0, remaining = K;      // uniform across the workgroup
   const bool take_all = !(K < L);
   if (!take_all) {
@@ -63,58 +63,69 @@ __device__ __forceinline__ void select_topk_in_registers(const uint32_t (&key)[K
       const int bins = pass == 2 ? 256 : 4096;
       const uint32_t digit_mask = bins - 1;
       const uint32_t mask = pass == 0 ? 0u : pass == 1 ? 0xfff00000u : 0xffffff00u;
-      for (int i = threadIdx.x; i < bins; i += kSelectThreads) hist[i] = 0;
-      __syncthreads();
-#pragma unroll
-      for (int j = 0; j < KPT; ++j) {
-        const bool act = t0 + j < L && (key[j] & mask) == prefix;
-        const uint32_t bin = (key[j] >> shift) & digit_mask;
-        // a wavefront whose active lanes all hit one bin (constant or zero scores) adds once
-        const uint64_t m = __ballot(act);
-        if (m == 0) continue;
-        const int leader = __ffsll(static_cast<long long>(m)) - 1;
-        const uint32_t leader_bin = __shfl(bin, leader, kWave);
-        if (__all(!act || bin == leader_bin)) {
-          if (lane == leader) atomicAdd(&hist[leader_bin], static_cast<uint32_t>(__popcll(m)));
-        } else if (act) {
-          atomicAdd(&hist[bin], 1u);
-        }
+      if (pass == 0) {                           // later passes find the bins zeroed by their last readers
+        for (int i = threadIdx.x; i < 4096; i += THREADS) hist[i] = 0;
+        __syncthreads();
       }
-      __syncthreads();
-      // thread t owns the bins (bins-1) - per*t - j, j < per, walking the digits downwards
-      const int per = bins / kSelectThreads;       // 4, or 0 for the 256-bin pass (then the first 256 threads own one)
-      uint32_t c[4] = {0u, 0u, 0u, 0u}, tot = 0;
-      if (per > 0) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { c[j] = hist[bins - 1 - 4 * threadIdx.x - j]; tot += c[j]; }
-      } else if (threadIdx.x < 256) {
-        c[0] = hist[255 - threadIdx.x];
-        tot = c[0];
-      }
-      uint32_t incl = wave_inclusive_sum(tot);   // inclusive scan over the workgroup: lanes, then wavefronts
-      if (lane == kWave - 1) wave_sum[0][wave] = incl;
-      __syncthreads();
-      uint32_t before = 0;
-      for (int w = 0; w < wave; ++w) before += wave_sum[0][w];
-      incl += before;
-      uint32_t above = incl - tot;           // keys in strictly higher digits than this thread's
-      if (above < remaining && incl >= remaining) {
-        const int nown = per > 0 ? 4 : 1;
-        for (int j = 0; j < nown; ++j) {
-          if (above < remaining && above + c[j] >= remaining) {
-            const uint32_t digit = per > 0 ? static_cast<uint32_t>(bins - 1 - 4 * threadIdx.x - j) : static_cast<uint32_t>(255 - threadIdx.x);
-            sh_prefix = prefix | (digit << shift);
-            sh_remaining = remaining - above;
-            above = remaining;               // stop: only one digit can match
-          } else {
-            above += c[j];
+      for (int c = 0; c < CH; ++c) {
+#pragma unroll
+        for (int j = 0; j < KPC; ++j) {
+          const bool act = c * kChunk + t0 + j < L && (key[c][j] & mask) == prefix;
+          const uint32_t bin = (key[c][j] >> shift) & digit_mask;
+          // a wavefront whose active lanes all hit one bin (constant or zero scores) adds once
+          const uint64_t m = __ballot(act);
+          if (m == 0) continue;
+          const int leader = __ffsll(static_cast<long long>(m)) - 1;
+          const uint32_t leader_bin = __shfl(bin, leader, kWave);
+          if (__all(!act || bin == leader_bin)) {
+            if (lane == leader) atomicAdd(&hist[leader_bin], static_cast<uint32_t>(__popcll(m)));
+          } else if (act) {
+            atomicAdd(&hist[bin], 1u);
           }
         }
       }
       __syncthreads();
-      prefix = sh_prefix;
-      remaining = sh_remaining;
+      // thread t owns the bins (bins-1) - per*t - j, j < per, walking the digits downwards; it reads them
+      // and leaves them zero for the next pass
+      constexpr int kPerWide = 4096 / THREADS;     // 4 or 8 bins per thread in the two 12-bit passes
+      const int per = pass == 2 ? (threadIdx.x < 256 ? 1 : 0) : kPerWide;
+      uint32_t cnt[kPerWide], tot = 0;
+#pragma unroll
+      for (int j = 0; j < kPerWide; ++j) {
+        cnt[j] = 0u;
+        if (j < per) {
+          uint32_t& slot = hist[bins - 1 - per * static_cast<int>(threadIdx.x) - j];
+          cnt[j] = slot;
+          slot = 0u;
+        }
+        tot += cnt[j];
+      }
+      uint32_t incl = wave_inclusive_sum(tot);   // inclusive scan over the workgroup: lanes, then wavefronts
+      if (lane == kWave - 1) lds.wave_sum[pass & 1][0][wave] = incl;
       __syncthreads();
+      uint32_t before = 0;
+      for (int w = 0; w < wave; ++w) before += lds.wave_sum[pass & 1][0][w];
+      incl += before;
+      uint32_t above = incl - tot;           // keys in strictly higher digits than this thread's
+      if (above < remaining && incl >= remaining) {
+#pragma unroll
+        for (int j = 0; j < kPerWide; ++j) {
+          if (j < per) {
+            if (above < remaining && above + cnt[j] >= remaining) {
+              const uint32_t digit = static_cast<uint32_t>(bins - 1 - per * static_cast<int>(threadIdx.x) - j);
+              lds.prefix[pass] = prefix | (digit << shift);
+              lds.remaining[pass] = remaining - above;
+              above = remaining;               // stop: only one digit can match
+            } else {
+              above += cnt[j];
+            }
+          }
+        }
+      }
+      __syncthreads();
+      prefix = lds.prefix[pass];
+      remaining = lds.remaining[pass];
     }
   } else {
     remaining = 0;
@@ -122,29 +133,48 @@ __device__ __forceinline__ void select_topk_in_registers(const uint32_t (&key)[K
   const uint32_t T = prefix;
   // remaining = how many keys equal to T are taken (lowest positions first)
 
-  uint32_t n_gt = 0, n_eq = 0;
+  // per chunk: how many of this thread's keys lie above T, and how many equal it
+  uint32_t n_gt[CH], n_eq[CH], s_gt[CH], s_eq[CH];
 #pragma unroll
-  for (int j = 0; j < KPT; ++j) {
-    const bool in = t0 + j < L;
-    n_gt += (in && (take_all || key[j] > T)) ? 1u : 0u;
-    n_eq += (in && !take_all && key[j] == T) ? 1u : 0u;
+  for (int c = 0; c < CH; ++c) {
+    n_gt[c] = n_eq[c] = 0;
+#pragma unroll
+    for (int j = 0; j < KPC; ++j) {
+      const bool in = c * kChunk + t0 + j < L;
+      n_gt[c] += (in && (take_all || key[c][j] > T)) ? 1u : 0u;
+      n_eq[c] += (in && !take_all && key[c][j] == T) ? 1u : 0u;
+    }
+    // exclusive scans of both counts over the workgroup, in position order (positions grow with the
+    // chunk first, then with the thread)
+    s_gt[c] = wave_inclusive_sum(n_gt[c]);
+    s_eq[c] = wave_inclusive_sum(n_eq[c]);
+    if (lane == kWave - 1) { lds.wave_sum[0][c][wave] = s_gt[c]; lds.wave_sum[1][c][wave] = s_eq[c]; }
   }
-  // exclusive scans of both counts over the workgroup, in position order
-  uint32_t s_gt = wave_inclusive_sum(n_gt), s_eq = wave_inclusive_sum(n_eq);
-  if (lane == kWave - 1) { wave_sum[0][wave] = s_gt; wave_sum[1][wave] = s_eq; }
   __syncthreads();
-  uint32_t b_gt = 0, b_eq = 0;
-  for (int w = 0; w < wave; ++w) { b_gt += wave_sum[0][w]; b_eq += wave_sum[1][w]; }
-  uint32_t gt_before = b_gt + s_gt - n_gt, eq_before = b_eq + s_eq - n_eq;
-  // output slot of a selected key = (# greater before it) + (# equal-and-taken before it)
+  uint32_t base_gt = 0, base_eq = 0;           // keys of earlier chunks
 #pragma unroll
-  for (int j = 0; j < KPT; ++j) {
-    const bool in = t0 + j < L;
-    const bool gt = in && (take_all || key[j] > T);
-    const bool eq = in && !take_all && key[j] == T;
-    if (gt || (eq && eq_before < remaining)) out[gt_before + min(eq_before, remaining)] = t0 + j;
-    gt_before += gt ? 1u : 0u;
-    eq_before += eq ? 1u : 0u;
+  for (int c = 0; c < CH; ++c) {
+    uint32_t b_gt = 0, b_eq = 0, t_gt = 0, t_eq = 0;
+    for (int w = 0; w < kWaves; ++w) {
+      const uint32_t a = lds.wave_sum[0][c][w], e = lds.wave_sum[1][c][w];
+      if (w < wave) { b_gt += a; b_eq += e; }
+      t_gt += a;
+      t_eq += e;
+    }
+    uint32_t gt_before = base_gt + b_gt + s_gt[c] - n_gt[c], eq_before = base_eq + b_eq + s_eq[c] - n_eq[c];
+    // output slot of a selected key = (# greater before it) + (# equal-and-taken before it)
+#pragma unroll
+    for (int j = 0; j < KPC; ++j) {
+      const int pos = c * kChunk + t0 + j;
+      const bool in = pos < L;
+      const bool gt = in && (take_all || key[c][j] > T);
+      const bool eq = in && !take_all && key[c][j] == T;
+      if (gt || (eq && eq_before < remaining)) out[gt_before + min(eq_before, remaining)] = pos;
+      gt_before += gt ? 1u : 0u;
+      eq_before += eq ? 1u : 0u;
+    }
+    base_gt += t_gt;
+    base_eq += t_eq;
   }
 }
 

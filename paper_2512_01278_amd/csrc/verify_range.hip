@@ -46,10 +46,12 @@ namespace {
 
 constexpr int kThreads = 64;                   // one wavefront per workgroup
 constexpr int kWindowPages = 64;               // page ids held per register: one per lane
+constexpr int kFinishMaxTokens = 32768;        // longest row whose Top-K the finish kernel selects itself
 
 struct RangeWs {
   int32_t* ctrl;        // [0] total units T
   int32_t* ureq;        // [B+1] first unit of request b (its heads follow each other)
+  int32_t* order;       // [pairs] (request, head) pairs in the order the finish kernel takes them: longest rows first
   float* part_m;        // [pairs + N][rows_pad]  log2 domain
   float* part_l;        // [pairs + N][rows_pad]
   float* part_o;        // [pairs + N][R][128]
@@ -73,6 +75,8 @@ __device__ __forceinline__ int range_of(int unit, int total, int n) {
 }
 
 // ---------------------------------------------------------------- plan ------
+// Unit prefix per request, and the order in which the finish kernel takes the (request, head) pairs:
+// longest requests first, so that the workgroups still running when the grid drains are short ones.
 __global__ __launch_bounds__(1024) void range_plan(KvView kv, RangeWs ws) {
   __shared__ int32_t scan[1024];
   __shared__ int32_t carry;
@@ -97,6 +101,24 @@ __global__ __launch_bounds__(1024) void range_plan(KvView kv, RangeWs ws) {
   if (threadIdx.x == 0) {
     ws.ureq[kv.batch] = carry;
     ws.ctrl[0] = carry;
+  }
+  // rank of every request by length (ties by index); batches beyond one workgroup keep their own order
+  if (kv.batch <= 1024) {
+    __syncthreads();
+    const int b = threadIdx.x;
+    const int len = b < kv.batch ? kv.seq_lens[b] : 0;
+    scan[threadIdx.x] = len;
+    __syncthreads();
+    if (b < kv.batch) {
+      int rank = 0;
+      for (int o = 0; o < kv.batch; ++o) {
+        const int lo = scan[o];
+        rank += (lo > len || (lo == len && o < b)) ? 1 : 0;
+      }
+      for (int g = 0; g < kv.num_kv_heads; ++g) ws.order[rank * kv.num_kv_heads + g] = b * kv.num_kv_heads + g;
+    }
+  } else {
+    for (int i = threadIdx.x; i < kv.batch * kv.num_kv_heads; i += 1024) ws.order[i] = i;
   }
 }
 
@@ -142,15 +164,17 @@ __device__ __forceinline__ void issue_tile(const KvView& kv, const Segment& sg, 
   constexpr int kPerGroup = kLoads / 2;
   const int esz = FP8 ? 1 : 2;
   const int last_page = (sg.L - 1) >> kv.page_shift;
+  // both 16-token groups of a tile lie in the same 64-page window (pages hold >= 16 tokens and a tile starts
+  // at a multiple of 32 tokens), so the window moves at most once per tile, before any row load is issued
+  if (min(tb >> kv.page_shift, last_page) / kWindowPages > pw.win) {          // wave-uniform
+    pw.pg_a = pw.pg_b;
+    pw.win += 1;
+    pw.pg_b = load_window(kv, sg.b, pw.win + 1, lane);
+  }
 #pragma unroll
   for (int grp = 0; grp < 2; ++grp) {
     const int tok0 = tb + 16 * grp;
     const int lp = min(tok0 >> kv.page_shift, last_page);
-    if (lp / kWindowPages > pw.win) {          // wave-uniform
-      pw.pg_a = pw.pg_b;
-      pw.win += 1;
-      pw.pg_b = load_window(kv, sg.b, pw.win + 1, lane);
-    }
     const int page = __builtin_amdgcn_readlane(pw.pg_a, lp - pw.win * kWindowPages);
     pages[grp] = page;
     const int64_t base = (static_cast<int64_t>(page) * kv.stride_page + static_cast<int64_t>(sg.g) * kv.stride_head +
@@ -311,6 +335,30 @@ __device__ __forceinline__ Flight issue_next(const KvView& kv, Cursor& c, const 
   issue_tile<FP8, true, WITH_V>(kv, c.sg, f.tb, c.pw, geo, lane, rk, rv, f.pages);
   advance_cursor(kv, c, lane);
   return f;
+}
+
+// The same in two steps, so that the K rows of the next tile can leave as soon as the K registers are free
+// and its V rows as soon as the V registers are: issue_next_k fills the flight and leaves the cursor on the
+// tile, issue_next_v sends the V loads of that tile and steps the cursor.
+template <bool FP8>
+__device__ __forceinline__ Flight issue_next_k(const KvView& kv, Cursor& c, const LaneGeom<FP8>& geo, int lane,
+                                               u32x4 (&rk)[TileRegs<FP8>::kLoads], u32x4 (&rv)[TileRegs<FP8>::kLoads]) {
+  Flight f;
+  f.valid = c.live;
+  f.sg = c.sg;
+  f.tb = c.tile * kTileTokens;
+  f.pages[0] = f.pages[1] = 0;
+  if (!c.live) return f;
+  issue_tile<FP8, true, false>(kv, c.sg, f.tb, c.pw, geo, lane, rk, rv, f.pages);
+  return f;
+}
+template <bool FP8>
+__device__ __forceinline__ void issue_next_v(const KvView& kv, Cursor& c, const Flight& f, const LaneGeom<FP8>& geo, int lane,
+                                             u32x4 (&rk)[TileRegs<FP8>::kLoads], u32x4 (&rv)[TileRegs<FP8>::kLoads]) {
+  if (!f.valid) return;
+  int pages[2];
+  issue_tile<FP8, false, true>(kv, f.sg, f.tb, c.pw, geo, lane, rk, rv, pages);
+  advance_cursor(kv, c, lane);
 }
 
 // ---------------------------------------------------------------- pass 1 ----
@@ -608,7 +656,7 @@ __global__ __launch_bounds__(256) void verify_o_merge_range(KvView kv, int n_q, 
 // p = e * exp2(m_tile - lse), and sums them over the rows: 2 bytes per (token, row) written and
 // read back, against the 2 * head_dim bytes per token of the second K read it replaces.
 //
-// A stashed value is 16 bits: e lies in [0, 1], so it is kept as 6 bits of exponent (2^-63 .. 1,
+// A stashed value is 16 bits: e lies in [0, 1], so it is kept as 6 bits of exponent (2^-62 .. 1,
 // smaller values become 0) and 10 bits of mantissa, rounded to nearest: relative error at most 2^-11
 // per term, hence at most 2^-11 (4.9e-4) on a score, which is a sum of positive terms.  That is inside
 // the 1e-3 the statistic is specified to, and far inside what Top-K needs; the two-pass variant keeps
@@ -618,11 +666,16 @@ __global__ __launch_bounds__(256) void verify_o_merge_range(KvView kv, int n_q, 
 // only the lanes of real rows (4 * nv, nv = R - 16 (RB - 1)); per lane 16 bytes = 8 values (tokens
 // 16 sub + 4 g4 + i, sub < 2, i < 4).
 __device__ __forceinline__ uint32_t stash_encode(float e) {
-  // round at the 10th mantissa bit and rebase the exponent to 2^-63 in one addition; what falls below becomes 0
+  // bits 28..13 of (e's float pattern - 64 exponent steps), rounded to nearest at the 10th mantissa bit.
+  // Exponent field 0 is kept for zero alone, so that the decoder's shift never makes a denormal: what lies
+  // below 2^-62 becomes 0.
   const int d = static_cast<int>(__float_as_uint(e)) + (0x1000 - 0x20000000);
-  return static_cast<uint32_t>(max(d, 0)) >> 13;                // [6-bit exponent | 10-bit mantissa]
+  return d >= 0x00800000 ? static_cast<uint32_t>(d) >> 13 : 0u;
 }
-__device__ __forceinline__ float stash_decode(uint32_t c) { return c ? __uint_as_float((c + 0x10000u) << 13) : 0.f; }
+// The stashed value times 2^-64: a plain shift into float position (0 stays 0).  Readers fold the 2^64 into
+// the per-row weight, see kStashBias.
+__device__ __forceinline__ float stash_decode_scaled(uint32_t c) { return __uint_as_float(c << 13); }
+constexpr float kStashBias = 64.f;
 
 __device__ __forceinline__ int stash_lane(int rb, int nblocks, int nv, int n, int g4, int lane) {
   return rb < nblocks - 1 ? rb * 64 + lane : (n < nv ? (nblocks - 1) * 64 + g4 * nv + n : -1);
@@ -724,11 +777,12 @@ __global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, con
     rows_to_lds<FP8, false>(rk, s_tile, lane);
     float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
     if constexpr (FP8) { half_scales(kv, cs.g, f.pages, kv.k_scale, ks); half_scales(kv, cs.g, f.pages, kv.v_scale, vs); }
+    f = issue_next_k<FP8>(kv, cur, geo, lane, rk, rv);       // the K registers are free: next tile's K rows leave now
     f32x4 s[2][RB];
     tile_qk_ldsq<RB>(s_tile, s_q, R, s, lane);
     if (tb + kTileTokens > cs.L) zero_tail_rows<FP8>(rv, tb, cs.L, geo);
     rows_to_lds<FP8, true>(rv, s_tile, lane);
-    f = issue_next<FP8, true>(kv, cur, geo, lane, rk, rv);
+    issue_next_v<FP8>(kv, cur, f, geo, lane, rk, rv);        // and its V rows once the V registers are
     const bool edge = tb + kTileTokens > cs.L - n_q;
     bf16x8 p[RB];
     uint8_t* st_base = ws.stash + static_cast<int64_t>(unit) * tile_lanes * 16;
@@ -1076,167 +1130,63 @@ __global__ __launch_bounds__(2 * kThreads, RB >= 3 ? 2 : 3) void verify_flash_pa
   else flash_pair_wave<RB, FP8, STASH, RB - kFirst, kFirst>(kv, q, n_q, ws, out, s_tile, s_q, 1);
 }
 
-// Probabilities from the stash: one wavefront per stretch of tiles, two tiles in flight.
-template <int RB>
-__global__ __launch_bounds__(kThreads, RB <= 2 ? 8 : 6) void verify_score_finalize(KvView kv, int n_q, RangeWs ws, float* scores,
-                                                                      int64_t score_stride) {
-  const int lane = threadIdx.x;
-  const int n = lane & 15, g4 = lane >> 4;
-  const int G = kv.num_q_heads / kv.num_kv_heads;
-  const int R = n_q * G;
-  const int nv = R - 16 * (RB - 1);
-  const int tile_lanes = (RB - 1) * 64 + 4 * nv;
-  float inv_r = 1.0f / static_cast<float>(queries_of(ws, 0, n_q) * G);      // set per request below
-  const int total = ws.ctrl[0];
-  const int u0 = range_begin(blockIdx.x, total, gridDim.x), u1 = range_begin(blockIdx.x + 1, total, gridDim.x);
-  if (u0 >= u1) return;
-  int b = find_request(ws, kv.batch, u0, lane);
-  int L = __builtin_amdgcn_readfirstlane(kv.seq_lens[b]);
-  int tiles = tiles_of_len(L);
-  const int rel = u0 - __builtin_amdgcn_readfirstlane(ws.ureq[b]);
-  int g = rel / tiles;
-  int tile = rel - g * tiles;
-  int sl[RB];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) sl[rb] = stash_lane(rb, RB, nv, n, g4, lane);
-  float lse2[RB];
-  auto load_lse = [&]() {
-    inv_r = 1.0f / static_cast<float>(queries_of(ws, b, n_q) * G);
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) lse2[rb] = ws.lse2[static_cast<int64_t>(b * kv.num_kv_heads + g) * (RB * 16) + 16 * rb + n];
-  };
-  load_lse();
-  u32x4 st[2][RB];
-  float mref[2][RB];
-  auto fetch = [&](int u, int buf) {
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      st[buf][rb] = u32x4{0u, 0u, 0u, 0u};
-      if (sl[rb] >= 0)
-        st[buf][rb] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ws.stash + (static_cast<int64_t>(u) * tile_lanes + sl[rb]) * 16));
-      mref[buf][rb] = ws.m_ref[static_cast<int64_t>(u) * (RB * 16) + 16 * rb + n];
-    }
-  };
-  auto tile_out = [&](int buf) {
-    f32x4 tot[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      const float w = fast_exp2(mref[buf][rb] - lse2[rb]);     // rows beyond R: lse = +inf, w = 0
-      const uint32_t h[4] = {st[buf][rb].x, st[buf][rb].y, st[buf][rb].z, st[buf][rb].w};
-#pragma unroll
-      for (int k = 0; k < 8; ++k) tot[k >> 2][k & 3] += stash_decode((h[k >> 1] >> (16 * (k & 1))) & 0xffffu) * w;
-    }
-    float* sdst = scores + (static_cast<int64_t>(b) * kv.num_kv_heads + g) * score_stride;
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) tot[sub][i] = row16_sum(tot[sub][i]) * inv_r;
-      const int tok0 = tile * kTileTokens + 16 * sub + 4 * g4;
-      if (n == 0) {
-        if (tok0 + 3 < L) {
-          *reinterpret_cast<f32x4*>(sdst + tok0) = tot[sub];
-        } else {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (tok0 + i < L) sdst[tok0 + i] = tot[sub][i];
-        }
-      }
-    }
-  };
-  auto advance = [&]() {
-    tile += 1;
-    if (tile == tiles) {
-      tile = 0;
-      g += 1;
-      if (g == kv.num_kv_heads) {
-        g = 0;
-        b = min(b + 1, kv.batch - 1);
-        L = __builtin_amdgcn_readfirstlane(kv.seq_lens[b]);
-        tiles = tiles_of_len(L);
-      }
-      load_lse();
-    }
-  };
-  fetch(u0, 0);
-  for (int u = u0; u < u1; u += 2) {
-    if (u + 1 < u1) fetch(u + 1, 1);
-    tile_out(0);
-    advance();
-    if (u + 1 >= u1) break;
-    if (u + 2 < u1) fetch(u + 2, 0);
-    tile_out(1);
-    advance();
-  }
-}
-
-// one workgroup per pair cut into several segments: O = sum over segments of exp2(m_seg - lse) O_seg
-__global__ __launch_bounds__(256) void verify_o_merge_flash(KvView kv, int n_q, RangeWs ws, uint16_t* out) {
-  const int pair = blockIdx.x;
-  const int b = pair / kv.num_kv_heads, g = pair - b * kv.num_kv_heads;
-  const int G = kv.num_q_heads / kv.num_kv_heads;
-  const int R = n_q * G;
-  const int total = ws.ctrl[0];
-  const int tiles = tiles_of_len(kv.seq_lens[b]);
-  const int u0 = ws.ureq[b] + g * tiles;
-  const int w0 = range_of(u0, total, ws.n_ranges), w1 = range_of(u0 + tiles - 1, total, ws.n_ranges);
-  if (w1 == w0) return;
-  const int Rb = queries_of(ws, b, n_q) * G;
-  for (int idx = threadIdx.x; idx < Rb * (kHeadDim / 4); idx += 256) {
-    const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
-    const float lse = ws.lse2[static_cast<int64_t>(pair) * ws.rows_pad + r];
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int w = w0; w <= w1; ++w) {
-      if (range_begin(w, total, ws.n_ranges) == range_begin(w + 1, total, ws.n_ranges)) continue;   // empty range
-      const float f = fast_exp2(ws.part_m[static_cast<int64_t>(pair + w) * ws.rows_pad + r] - lse);
-      acc += *reinterpret_cast<const f32x4*>(ws.part_o + (static_cast<int64_t>(pair + w) * R + r) * kHeadDim + 4 * d4) * f;
-    }
-    const int i = r / G, hg = r - i * G;
-    uint16_t* dst = out + ((static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg) * kHeadDim;
-    u32x2 pk;
-    pk.x = pack2(acc.x, acc.y);
-    pk.y = pack2(acc.z, acc.w);
-    *reinterpret_cast<u32x2*>(dst + 4 * d4) = pk;
-  }
-}
-
-// ------------------------------------------------ finish with selection -----
-// Scores and Top-K in one kernel: one 1024-thread workgroup per (request, KV head) rebuilds the
-// pair's scores from the stash into LDS (tiles round-robin over its 16 wavefronts, two in flight
-// each), writes them out if the caller wants them, and selects straight from LDS -- the statistic
-// never makes the round trip through HBM between two launches (paper Section 4.1: identification
-// from the verification's own intermediates without extra memory traffic).
-template <int RB, int KPT>
-__global__ __launch_bounds__(kSelectThreads) void verify_select_finish(KvView kv, int n_q, RangeWs ws, float* scores,
-                                                                       int64_t score_stride, SelectOut sel) {
-  extern __shared__ __attribute__((aligned(16))) float s_scores[];      // kSelectThreads * KPT positions
-  __shared__ SelectLds lds;
-  const int pair = blockIdx.x;
+// ------------------------------------------------ finish ---------------------
+// Everything that needs the whole pair, in one kernel: one workgroup per (request, KV head), longest
+// rows first.
+//   1. the log-sum-exp of every row from the (m, l) of the pair's segments;
+//   2. O of a pair that was cut into several segments: sum over segments of exp2(m_seg - lse) O_seg
+//      (a pair inside one range was finished by the pass itself);
+//   3. the score statistic from the stash, scores = mean over rows of e * exp2(m_tile - lse): wavefronts take
+//      the pair's tiles in turn, two in flight each, and leave the scores of one chunk of tokens at a time in
+//      LDS, from where every thread takes 8 consecutive ones as sort keys into registers (and writes them out
+//      if the caller wants the statistic itself);
+//   4. SELECT: Top-K of the keys in registers (topk_core.hpp) -- the statistic makes no round trip through
+//      memory between two launches (paper Section 4.1: identification from the verification's own
+//      intermediates).
+// Rows of up to CH * THREADS * 8 tokens; without SELECT any length (the chunk loop is then a run-time one).
+template <int RB, int THREADS, int CH, bool SELECT>
+__global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, RangeWs ws, uint16_t* out, float* lse_out,
+                                                         float* scores, int64_t score_stride, SelectOut sel) {
+  constexpr int KPC = 8;
+  constexpr int kChunk = THREADS * KPC;                      // tokens whose scores LDS holds at a time
+  constexpr int kChunkTiles = kChunk / kTileTokens;
+  constexpr int kWaves = THREADS / kWave;
+  __shared__ __attribute__((aligned(16))) float s_scores[kChunk];
+  __shared__ float s_lse[RB * 16];
+  __shared__ SelectLds<THREADS, CH> lds;
+  const int pair = ws.order[blockIdx.x];
   const int b = pair / kv.num_kv_heads, g = pair - b * kv.num_kv_heads;
   const int L = kv.seq_lens[b];
   const int tiles = tiles_of_len(L);
+  const int G = kv.num_q_heads / kv.num_kv_heads;
+  const int R = n_q * G;
+  const int Rb = queries_of(ws, b, n_q) * G;
+  constexpr int rows = RB * 16;
+  const int total = ws.ctrl[0];
   const int u0 = ws.ureq[b] + g * tiles;
-  const int K = max(0, min(min(sel.budgets[b], L), sel.max_budget));
-  int32_t* out_idx = sel.indices + static_cast<int64_t>(pair) * sel.max_budget;
-  if (g == 0 && threadIdx.x == 0) sel.counts[b] = K;
-  for (int j = K + threadIdx.x; j < sel.max_budget; j += kSelectThreads) out_idx[j] = -1;
-  if (K == 0 && !scores) return;
+  const int w0 = range_of(u0, total, ws.n_ranges), w1 = range_of(u0 + tiles - 1, total, ws.n_ranges);
+  int K = 0;
+  int32_t* out_idx = nullptr;
+  if constexpr (SELECT) {
+    K = max(0, min(min(sel.budgets[b], L), sel.max_budget));
+    out_idx = sel.indices + static_cast<int64_t>(pair) * sel.max_budget;
+    if (g == 0 && threadIdx.x == 0) sel.counts[b] = K;
+    for (int j = K + threadIdx.x; j < sel.max_budget; j += THREADS) out_idx[j] = -1;
+  }
 
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int n = lane & 15, g4 = lane >> 4;
-  const int G = kv.num_q_heads / kv.num_kv_heads;
-  const int R = n_q * G;
   const int nv = R - 16 * (RB - 1);
   const int tile_lanes = (RB - 1) * 64 + 4 * nv;
-  const float inv_r = 1.0f / static_cast<float>(queries_of(ws, b, n_q) * G);
+  const bool want_scores = SELECT || scores;
+
+  // The stash stream: wavefronts take the tiles of a chunk in turn, kBufs tiles in flight each.
+  constexpr int kBufs = THREADS >= 1024 ? 2 : 4;       // (a 1024-thread workgroup has 128 registers per lane)
   int sl[RB];
-  float lse2[RB];
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    sl[rb] = stash_lane(rb, RB, nv, n, g4, lane);
-    lse2[rb] = ws.lse2[static_cast<int64_t>(pair) * (RB * 16) + 16 * rb + n];
-  }
-  u32x4 st[2][RB];
-  float mref[2][RB];
+  for (int rb = 0; rb < RB; ++rb) sl[rb] = stash_lane(rb, RB, nv, n, g4, lane);
+  u32x4 st[kBufs][RB];
+  float mref[kBufs][RB];
   auto fetch = [&](int tile, int buf) {
     const int64_t u = u0 + tile;
 #pragma unroll
@@ -1244,63 +1194,177 @@ __global__ __launch_bounds__(kSelectThreads) void verify_select_finish(KvView kv
       st[buf][rb] = u32x4{0u, 0u, 0u, 0u};
       if (sl[rb] >= 0)
         st[buf][rb] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ws.stash + (u * tile_lanes + sl[rb]) * 16));
-      mref[buf][rb] = ws.m_ref[u * (RB * 16) + 16 * rb + n];
+      mref[buf][rb] = __builtin_nontemporal_load(ws.m_ref + u * rows + 16 * rb + n);
     }
   };
-  auto tile_out = [&](int tile, int buf) {
+  auto prime = [&](int c) {                              // first tiles of chunk c on their way
+    const int t_begin = c * kChunkTiles, t_end = min(tiles, t_begin + kChunkTiles);
+#pragma unroll
+    for (int i = 0; i < kBufs; ++i)
+      if (t_begin + wave + i * kWaves < t_end) fetch(t_begin + wave + i * kWaves, i);
+  };
+  if (want_scores) prime(0);                           // needs nothing of steps 1 and 2: in flight meanwhile
+
+  // 1. log-sum-exp per row (log2 domain).  Rows beyond the request's own, and rows that see no token at all,
+  // get +inf: their probabilities vanish wherever the log-sum-exp is applied.
+  // 2. O of a pair cut into several segments.  The partials of up to kSegs segments are fetched before the
+  // log-sum-exp is known (every thread owns up to kOuts pieces of 4 dims), so both waits overlap.
+  constexpr int kSegs = THREADS >= 1024 ? 2 : 4;
+  constexpr int kOuts = (RB * 16 * (kHeadDim / 4) + THREADS - 1) / THREADS;
+  const int nseg = w1 - w0 + 1;
+  const bool split = w1 > w0;
+  const bool early = split && nseg <= kSegs && total >= ws.n_ranges;     // (no empty ranges when there are as many units as ranges)
+  f32x4 po[kOuts][kSegs];
+  float pm[kOuts][kSegs];
+  if (early) {
+#pragma unroll
+    for (int o = 0; o < kOuts; ++o) {
+      const int idx = threadIdx.x + o * THREADS;
+      const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
+#pragma unroll
+      for (int sg = 0; sg < kSegs; ++sg) {
+        po[o][sg] = f32x4{0.f, 0.f, 0.f, 0.f};
+        pm[o][sg] = -INFINITY;
+        if (r < Rb && sg < nseg) {
+          po[o][sg] = *reinterpret_cast<const f32x4*>(ws.part_o + (static_cast<int64_t>(pair + w0 + sg) * R + r) * kHeadDim + 4 * d4);
+          pm[o][sg] = ws.part_m[static_cast<int64_t>(pair + w0 + sg) * rows + r];
+        }
+      }
+    }
+  }
+  if (threadIdx.x < rows) {
+    const int row = threadIdx.x;
+    float m = -INFINITY, l = 0.f;
+    for (int w = w0; w <= w1; ++w) {
+      // with fewer units than ranges some ranges are empty and own no segment
+      if (range_begin(w, total, ws.n_ranges) == range_begin(w + 1, total, ws.n_ranges)) continue;
+      const float mc = ws.part_m[static_cast<int64_t>(pair + w) * rows + row];
+      const float lc = ws.part_l[static_cast<int64_t>(pair + w) * rows + row];
+      const float mn = fmaxf(m, mc);
+      const float mu = (mn == -INFINITY) ? 0.f : mn;
+      l = l * fast_exp2(m - mu) + lc * fast_exp2(mc - mu);
+      m = mn;
+    }
+    const bool live = row < Rb && l > 0.f;
+    const float v = live ? m + log2f(l) : INFINITY;
+    s_lse[row] = v;
+    if (lse_out && row < Rb) {
+      const int i = row / G, hg = row - i * G;
+      lse_out[(static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg] = live ? v * kLn2 : -INFINITY;
+    }
+  }
+  __syncthreads();
+  if (split) {
+    auto store_o = [&](int r, int d4, const f32x4& acc) {
+      const int i = r / G, hg = r - i * G;
+      uint16_t* dst = out + ((static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg) * kHeadDim;
+      u32x2 pk;
+      pk.x = pack2(acc.x, acc.y);
+      pk.y = pack2(acc.z, acc.w);
+      *reinterpret_cast<u32x2*>(dst + 4 * d4) = pk;
+    };
+    if (early) {
+#pragma unroll
+      for (int o = 0; o < kOuts; ++o) {
+        const int idx = threadIdx.x + o * THREADS;
+        const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
+        if (r < Rb) {
+          const float lse = s_lse[r];
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int sg = 0; sg < kSegs; ++sg) acc += po[o][sg] * fast_exp2(pm[o][sg] - lse);   // absent segments: exp2(-inf) = 0
+          store_o(r, d4, acc);
+        }
+      }
+    } else {
+      for (int idx = threadIdx.x; idx < Rb * (kHeadDim / 4); idx += THREADS) {
+        const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
+        const float lse = s_lse[r];
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int w = w0; w <= w1; ++w) {
+          if (range_begin(w, total, ws.n_ranges) == range_begin(w + 1, total, ws.n_ranges)) continue;   // empty range
+          const float f = fast_exp2(ws.part_m[static_cast<int64_t>(pair + w) * rows + r] - lse);
+          acc += *reinterpret_cast<const f32x4*>(ws.part_o + (static_cast<int64_t>(pair + w) * R + r) * kHeadDim + 4 * d4) * f;
+        }
+        store_o(r, d4, acc);
+      }
+    }
+  }
+  if (!want_scores) return;
+
+  // 3. scores of the pair, chunk by chunk
+  const float log2_inv_r = -log2f(static_cast<float>(Rb));
+  float bias[RB];                                      // per row: -lse + the stash's 2^64 + log2(1 / rows)
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) bias[rb] = kStashBias + log2_inv_r - s_lse[16 * rb + n];   // -inf for rows that carry no weight
+  auto tile_out = [&](int slot, int buf) {             // slot = tile within the chunk
     f32x4 tot[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      const float w = fast_exp2(mref[buf][rb] - lse2[rb]);     // rows beyond R: lse = +inf, w = 0
+      const float w = fast_exp2(mref[buf][rb] + bias[rb]);
       const uint32_t h[4] = {st[buf][rb].x, st[buf][rb].y, st[buf][rb].z, st[buf][rb].w};
 #pragma unroll
-      for (int k = 0; k < 8; ++k) tot[k >> 2][k & 3] += stash_decode((h[k >> 1] >> (16 * (k & 1))) & 0xffffu) * w;
+      for (int k = 0; k < 8; ++k) {
+        const uint32_t c = (k & 1) ? (h[k >> 1] >> 16) : (h[k >> 1] & 0xffffu);
+        tot[k >> 2][k & 3] = fmaf(stash_decode_scaled(c), w, tot[k >> 2][k & 3]);
+      }
     }
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) tot[sub][i] = row16_sum(tot[sub][i]) * inv_r;
-      if (n == 0) *reinterpret_cast<f32x4*>(s_scores + tile * kTileTokens + 16 * sub + 4 * g4) = tot[sub];
+      for (int i = 0; i < 4; ++i) tot[sub][i] = row16_sum(tot[sub][i]);
+      if (n == 0) *reinterpret_cast<f32x4*>(s_scores + slot * kTileTokens + 16 * sub + 4 * g4) = tot[sub];
     }
   };
-  {
-    int tile = wave;
-    if (tile < tiles) fetch(tile, 0);
-    while (tile < tiles) {
-      if (tile + kSelectWaves < tiles) fetch(tile + kSelectWaves, 1);
-      tile_out(tile, 0);
-      tile += kSelectWaves;
-      if (tile >= tiles) break;
-      if (tile + kSelectWaves < tiles) fetch(tile + kSelectWaves, 0);
-      tile_out(tile, 1);
-      tile += kSelectWaves;
-    }
-  }
-  __syncthreads();
-  if (scores) {
-    float* sdst = scores + static_cast<int64_t>(pair) * score_stride;
-    for (int t = 4 * threadIdx.x; t < L; t += 4 * kSelectThreads) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(s_scores + t);
-      if (t + 3 < L) {
-        *reinterpret_cast<f32x4*>(sdst + t) = v;
-      } else {
+  float* sdst = scores ? scores + static_cast<int64_t>(pair) * score_stride : nullptr;
+  uint32_t key[CH][KPC];
+  auto chunk = [&](int c, uint32_t (&keys)[KPC]) {
+    const int t_begin = c * kChunkTiles, t_end = min(tiles, t_begin + kChunkTiles);
+    if (c > 0) prime(c);
+    for (int tile = t_begin + wave; tile < t_end;) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (t + i < L) sdst[t + i] = v[i];
+      for (int i = 0; i < kBufs; ++i) {
+        if (tile < t_end) {
+          tile_out(tile - t_begin, i);
+          if (tile + kBufs * kWaves < t_end) fetch(tile + kBufs * kWaves, i);      // buffer i is free again
+          tile += kWaves;
+        }
       }
     }
-  }
-  if (K == 0) return;
-  const int t0 = threadIdx.x * KPT;
-  uint32_t key[KPT];
+    __syncthreads();
+    const int p0 = c * kChunk + static_cast<int>(threadIdx.x) * KPC;      // this thread's 8 positions
 #pragma unroll
-  for (int j = 0; j < KPT; j += 4) {
-    f32x4 v = {0.f, 0.f, 0.f, 0.f};
-    if (t0 + j < tiles * kTileTokens) v = *reinterpret_cast<const f32x4*>(s_scores + t0 + j);
+    for (int j = 0; j < KPC; j += 4) {
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (p0 + j < t_end * kTileTokens) v = *reinterpret_cast<const f32x4*>(s_scores + static_cast<int>(threadIdx.x) * KPC + j);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) key[j + i] = order_key(v[i]);
+      for (int i = 0; i < 4; ++i) keys[j + i] = order_key(v[i]);
+      if (sdst) {
+        if (p0 + j + 3 < L) {
+          *reinterpret_cast<f32x4*>(sdst + p0 + j) = v;
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (p0 + j + i < L) sdst[p0 + j + i] = v[i];
+        }
+      }
+    }
+    __syncthreads();                                   // the next chunk overwrites the scores
+  };
+  if constexpr (SELECT) {
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      if (c * kChunk < L) {                            // uniform over the workgroup
+        chunk(c, key[c]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < KPC; ++j) key[c][j] = 0u;
+      }
+    }
+    if (K > 0) select_topk_in_registers<THREADS, KPC, CH>(key, L, K, out_idx, lds);
+  } else {
+    for (int c = 0; c * kChunk < L; ++c) chunk(c, key[0]);
   }
-  select_topk_in_registers<KPT>(key, t0, L, K, out_idx, lds);
 }
 
 // ---------------------------------------------------------------- host ------
@@ -1336,6 +1400,7 @@ RangeWs carve(const KvView& kv, int n_q, void* workspace, size_t* total_bytes) {
   RangeWs w;
   w.ctrl = reinterpret_cast<int32_t*>(take(64 * 4));
   w.ureq = reinterpret_cast<int32_t*>(take((static_cast<size_t>(kv.batch) + 1) * 4));
+  w.order = reinterpret_cast<int32_t*>(take(pairs * 4));
   w.part_m = reinterpret_cast<float*>(take(slots * rpad * 4));
   w.part_l = reinterpret_cast<float*>(take(slots * rpad * 4));
   w.part_o = reinterpret_cast<float*>(take(slots * R * kHeadDim * 4));
@@ -1380,36 +1445,19 @@ hipError_t run(const VerifyArgs& a, hipStream_t st) {
       }
     }
     {
-      KernelTimer t("verify_lse_combine", st);
-      hipLaunchKernelGGL(verify_lse_combine_range, dim3((pairs * ws.rows_pad + 255) / 256), dim3(256), 0, st, kv, a.n_q, ws, a.lse);
-    }
-    if (a.select) {
-      KernelTimer t("verify_select_finish", st);
-      const SelectOut& sel = *a.select;
-#define PILLAR_SELECT(KPT)                                                                                                   \
-  {                                                                                                                          \
-    const size_t lds = static_cast<size_t>(kSelectThreads) * KPT * sizeof(float);                                           \
-    static bool attr_done = false;                                                                                           \
-    if (!attr_done) {                                                                                                        \
-      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_select_finish<RB, KPT>),               \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));          \
-      if (e != hipSuccess) return e;                                                                                         \
-      attr_done = true;                                                                                                      \
-    }                                                                                                                        \
-    hipLaunchKernelGGL((verify_select_finish<RB, KPT>), dim3(pairs), dim3(kSelectThreads), lds, st, kv, a.n_q, ws, a.scores, \
-                       a.score_stride, sel);                                                                                \
-  }
-      if (kv.max_seq_len <= kSelectThreads * 8) PILLAR_SELECT(8)
-      else PILLAR_SELECT(16)
-#undef PILLAR_SELECT
-    } else if (a.scores) {
-      KernelTimer t("verify_score_finalize", st);
-      hipLaunchKernelGGL((verify_score_finalize<RB>), dim3(32 * num_cus()), dim3(kThreads), 0, st, kv, a.n_q, ws, a.scores,
-                         a.score_stride);
-    }
-    {
-      KernelTimer t("verify_o_merge", st);
-      hipLaunchKernelGGL(verify_o_merge_flash, dim3(pairs), dim3(256), 0, st, kv, a.n_q, ws, out);
+      // one workgroup per pair: log-sum-exp, O of split pairs, scores, selection
+      KernelTimer t("verify_finish", st);
+      SelectOut none{};
+      const SelectOut& sel = a.select ? *a.select : none;
+#define PILLAR_FINISH(THREADS, CH, SELECT)                                                                                    \
+  hipLaunchKernelGGL((verify_finish<RB, THREADS, CH, SELECT>), dim3(pairs), dim3(THREADS), 0, st, kv, a.n_q, ws, out, a.lse, \
+                     a.scores, a.score_stride, sel)
+      if (!a.select) PILLAR_FINISH(512, 1, false);
+      else if (kv.max_seq_len <= 4096) PILLAR_FINISH(512, 1, true);
+      else if (kv.max_seq_len <= 8192) PILLAR_FINISH(512, 2, true);
+      else if (kv.max_seq_len <= 16384) PILLAR_FINISH(1024, 2, true);
+      else PILLAR_FINISH(1024, 4, true);
+#undef PILLAR_FINISH
     }
     return hipGetLastError();
   }
@@ -1456,9 +1504,8 @@ bool verify_range_supported(const VerifyArgs& a) {
 }
 
 bool verify_select_fused(const VerifyArgs& a) {
-  // rows of more than 16 K tokens would need 128 KB of LDS per workgroup, one workgroup per compute unit:
-  // measured slower than the two kernels (config 5: 167 against 139 us), so those take the two steps
-  return a.select && verify_range_supported(a) && !a.exact_scores && a.kv.max_seq_len <= kSelectThreads * 16;
+  // the finish kernel keeps the keys of a row in registers: up to 4 chunks of 8192 tokens; longer rows take the two steps
+  return a.select && verify_range_supported(a) && !a.exact_scores && a.kv.max_seq_len <= kFinishMaxTokens;
 }
 
 size_t verify_range_workspace(const KvView& kv, int n_q) {
