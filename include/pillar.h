@@ -195,11 +195,12 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
  * not cause an allocation: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
  * result bits as pillar_sparse_decode, but the partial results of index lists
- * that are split over several wavefronts go to a 32 MiB array inside the
+ * longer than one workgroup's span of 512 rows go to a 32 MiB array inside the
  * library (one copy per GPU, held until the process ends) instead of a
  * workspace.  A shape whose pillar_sparse_decode would need more than those
- * 32 MiB (batch * Hkv * splits * G rows of 128 floats; about 60000 (request, KV
- * head, split) units at G = 4) returns PILLAR_ETOOLARGE and launches nothing.
+ * 32 MiB (batch * Hkv * ceil(max_budget / 512) spans of G rows of 128 floats;
+ * about 15000 spans at G = 4; lists of up to 512 rows need none) returns
+ * PILLAR_ETOOLARGE and launches nothing.
  * Calls no allocator.  All calls on one GPU share the one array: two such
  * calls that overlap in time on the same GPU (different streams) race; order
  * them.  The first call on a device looks the array's address up; make it

@@ -35,8 +35,8 @@ int  pillar_profile_read(pillar_kernel_time* entries, int cap);
 /* Launch-shape knobs for sweeps (process-wide, not thread-safe against running
  * calls; none of them changes a result bit).  Known names: "verify_waves"
  * (wavefronts per compute unit that the verification pass is divided among,
- * 1..8) and "decode_rows" (rows of the index list per wavefront of the draft
- * kernel, a multiple of 32 up to 4096).  A value of 0 restores the default.  Returns
+ * 1..8) and "decode_rows" (rows of the index list per workgroup of the draft
+ * kernel, a multiple of 32 up to 4096; default 512).  A value of 0 restores the default.  Returns
  * PILLAR_EINVAL for an unknown name or a value outside the knob's range. */
 int pillar_set_option(const char* name, int64_t value);
 

@@ -9,13 +9,15 @@
 // in flight as early as possible; the G query rows of the group ride along as
 // one 16-row MFMA block (the tile engine of mfma_tile.hpp with R = G).
 //
-// One single-wavefront workgroup per (request, KV head, split of the index
-// list): a split is one or a few 32-row tiles, sized so that the grid is about
-// two rounds of what the chip holds at 16 wavefronts per compute unit.  With so
-// little work per wavefront the dependent chain index -> page id -> row is the
-// whole cost, and many independent wavefronts are what overlaps it.  Lists that
-// fit one split are finished in the kernel; longer lists leave (max, sum, O)
-// partials that a second small kernel combines.
+// One workgroup of kWaves wavefronts per (request, KV head, span of the index
+// list): the wavefronts take the 32-row tiles of the span in turn, each with the
+// gather of its next tile (index -> page id) resolved while the rows of the
+// current one are in flight, and combine their (max, sum, O) through LDS at the
+// end, so a list that fits one span (512 rows) is finished by the one launch.
+// Longer lists leave one partial per span that a second small kernel combines.
+// The count of a request and its first index entries are fetched side by side:
+// the chain a wavefront waits through before its first row load is then
+// count | index -> page id -> row.
 #include <algorithm>
 #include <mutex>
 
@@ -27,6 +29,9 @@ namespace {
 
 constexpr int kThreads = 64;                   // one wavefront per workgroup
 constexpr int kMergeThreads = 256;
+constexpr int kWaves = 4;                      // wavefronts per workgroup of the draft kernel
+constexpr int kGroupThreads = kWaves * kThreads;
+constexpr int kSpanRows = 512;                 // rows of an index list one workgroup takes
 
 struct DecWs {
   float* part_m;   // [B][Hkv][nsplit][16]  log2 domain
@@ -34,41 +39,41 @@ struct DecWs {
   float* part_o;   // [B][Hkv][nsplit][G][128]
 };
 
-struct Gather {
-  int tok;      // lane j < 32: token position of row j of the tile
-  int page;     // its page id
-  float ks, vs; // fp8 only: dequantisation scales of that row
+// Resolved rows of two tiles: lane j < 32 holds row j of one tile, lane 32 + j row j of another.
+struct Rows {
+  uint32_t off16;  // byte offset of the row in a pool, in units of 16 bytes (rows are 16-byte aligned)
+  float ks, vs;    // fp8 only: dequantisation scales of that row
 };
 
+// token position -> page id -> row offset (and, for fp8, the scales of its page)
 template <bool FP8>
-__device__ __forceinline__ Gather load_gather(const KvView& kv, const int32_t* list, int b, int g, int j_first, int j_end, int lane) {
-  Gather gt;
-  const int j = min(j_first + (lane & 31), j_end - 1);      // rows past the end repeat the last one (masked later)
-  gt.tok = list[j];
-  gt.page = kv.block_table[static_cast<int64_t>(b) * kv.block_table_stride + (gt.tok >> kv.page_shift)];
-  gt.ks = gt.vs = 1.f;
+__device__ __forceinline__ Rows resolve_rows(const KvView& kv, int b, int g, int tok) {
+  const int esz = FP8 ? 1 : 2;
+  Rows r;
+  const int page = kv.block_table[static_cast<int64_t>(b) * kv.block_table_stride + (tok >> kv.page_shift)];
+  const int64_t off = (static_cast<int64_t>(page) * kv.stride_page + static_cast<int64_t>(g) * kv.stride_head +
+                       static_cast<int64_t>(tok & (kv.page_size - 1)) * kv.stride_slot) * esz;
+  r.off16 = static_cast<uint32_t>(off >> 4);
+  r.ks = r.vs = 1.f;
   if constexpr (FP8) {
-    gt.ks = kv.k_scale[static_cast<int64_t>(gt.page) * kv.num_kv_heads + g];
-    gt.vs = kv.v_scale[static_cast<int64_t>(gt.page) * kv.num_kv_heads + g];
+    r.ks = kv.k_scale[static_cast<int64_t>(page) * kv.num_kv_heads + g];
+    r.vs = kv.v_scale[static_cast<int64_t>(page) * kv.num_kv_heads + g];
   }
-  return gt;
+  return r;
 }
 
+// sends the row loads of the tile in half `half` (0: lanes 0..31, 1: lanes 32..63) of `r`
 template <bool FP8>
-__device__ __forceinline__ void issue_gather(const KvView& kv, int g, const Gather& gt, TileRegs<FP8>& t, int lane) {
+__device__ __forceinline__ void issue_rows(const KvView& kv, const Rows& r, int half, TileRegs<FP8>& t, int lane) {
   constexpr int kRowsPerLoad = FP8 ? 8 : 4;
   constexpr int kLanesPerRow = FP8 ? 8 : 16;
   const int col = (lane % kLanesPerRow) * 16;
   const char* kp = static_cast<const char*>(kv.k_pool);
   const char* vp = static_cast<const char*>(kv.v_pool);
-  const int esz = FP8 ? 1 : 2;
 #pragma unroll
   for (int u = 0; u < TileRegs<FP8>::kLoads; ++u) {
     const int row = kRowsPerLoad * u + lane / kLanesPerRow;
-    const int tok = __shfl(gt.tok, row, 64);
-    const int page = __shfl(gt.page, row, 64);
-    const int64_t off = (static_cast<int64_t>(page) * kv.stride_page + static_cast<int64_t>(g) * kv.stride_head +
-                         static_cast<int64_t>(tok & (kv.page_size - 1)) * kv.stride_slot) * esz + col;
+    const uint64_t off = (static_cast<uint64_t>(__shfl(r.off16, 32 * half + row, 64)) << 4) + col;
     t.k[u] = *reinterpret_cast<const u32x4*>(kp + off);
     t.v[u] = *reinterpret_cast<const u32x4*>(vp + off);
   }
@@ -79,122 +84,171 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 }
 
 template <bool FP8>
-__global__ __launch_bounds__(kThreads, 3) void decode_split_mfma(DecodeArgs a, DecWs ws, int split_rows, int nsplit_max) {
-  // one tile buffer: the K rows, then (once S^T is done) the V rows of the same tile
-  __shared__ __attribute__((aligned(16))) uint8_t s_tile[kVTileBytes];
+__global__ __launch_bounds__(kGroupThreads, 3) void decode_span_mfma(DecodeArgs a, DecWs ws, int span_rows, int nspan_max) {
+  // per wavefront one tile buffer: the K rows, then (once S^T is done) the V rows of the same tile; at the end
+  // its (max, sum, O) for the combine
+  __shared__ __attribute__((aligned(16))) uint8_t s_tiles[kWaves][kVTileBytes];
   const KvView& kv = a.kv;
   const int b = blockIdx.z, g = blockIdx.y, sp = blockIdx.x;
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & (kThreads - 1), wave = threadIdx.x / kThreads;
   const int n = lane & 15, g4 = lane >> 4;
   const int G = kv.num_q_heads / kv.num_kv_heads;
+  uint8_t* s_tile = s_tiles[wave];
+  const int32_t* list = a.indices + (static_cast<int64_t>(b) * kv.num_kv_heads + g) * a.max_budget;
+  const int j_begin = sp * span_rows;
+  // The index entries of the first four tiles of this wavefront (tiles wave, wave + kWaves, ...; register q holds
+  // tile 2q in lanes 0..31 and tile 2q + 1 in lanes 32..63) leave together with the count: entries up to
+  // max_budget exist, which of them count is decided when both are here.
+  auto entry_of = [&](int round, int q) {
+    const int tile = wave + kWaves * (4 * round + 2 * q + (lane >> 5));
+    return j_begin + tile * kTileTokens + (lane & 31);
+  };
+  int tok[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) tok[q] = list[min(entry_of(0, q), a.max_budget - 1)];
   const int count = min(max(a.counts[b], 0), a.max_budget);
   uint16_t* out = static_cast<uint16_t*>(a.out);
   if (count == 0) {
     if (sp == 0) {
-      for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kThreads)
+      for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kGroupThreads)
         out[(static_cast<int64_t>(b) * kv.num_q_heads + g * G) * kHeadDim + idx] = 0;
       if (a.lse && threadIdx.x < G) a.lse[static_cast<int64_t>(b) * kv.num_q_heads + g * G + threadIdx.x] = -INFINITY;
     }
     return;
   }
-  const int j_begin = sp * split_rows;
   if (j_begin >= count) return;
-  const int j_end = min(count, j_begin + split_rows);
-  const int nsplit = (count + split_rows - 1) / split_rows;
-  const int ntiles = (j_end - j_begin + kTileTokens - 1) / kTileTokens;
-  const int32_t* list = a.indices + (static_cast<int64_t>(b) * kv.num_kv_heads + g) * a.max_budget;
+  const int j_end = min(count, j_begin + span_rows);
+  const int nspan = (count + span_rows - 1) / span_rows;
+  const int ntiles = (j_end - j_begin + kTileTokens - 1) / kTileTokens;       // of the span
   const float c2 = kv.sm_scale * kLog2e;
-
-  Gather cur = load_gather<FP8>(kv, list, b, g, j_begin, j_end, lane);
-  // B operand: lane (n, g4) holds Q[row n][32s + 8 g4 .. +7]
-  bf16x8 qf[1][4];
-  const uint16_t* qrow = static_cast<const uint16_t*>(a.q) + (static_cast<int64_t>(b) * kv.num_q_heads + g * G + n) * kHeadDim;
-#pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (n < G) v = *reinterpret_cast<const u32x4*>(qrow + 32 * s + 8 * g4);
-    qf[0][s] = as_bf16x8(v);
-  }
-  TileRegs<FP8> regs;
-  issue_gather<FP8>(kv, g, cur, regs, lane);
 
   f32x4 o[1][8];
 #pragma unroll
   for (int d = 0; d < 8; ++d) o[0][d] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;
-  for (int ti = 0; ti < ntiles; ++ti) {
-    const int jb = j_begin + ti * kTileTokens;
-    const bool more = ti + 1 < ntiles;
-    Gather nxt = cur;
-    if (more) nxt = load_gather<FP8>(kv, list, b, g, jb + kTileTokens, j_end, lane);
-    rows_to_lds<FP8, false>(regs.k, s_tile, lane);
-    f32x4 s[2][1];
-    tile_qk<1>(s_tile, qf, s, lane);
-    rows_to_lds<FP8, true>(regs.v, s_tile, lane);
-    if (more) issue_gather<FP8>(kv, g, nxt, regs, lane);
-    f32x4 vsc[2];
+  if (wave < ntiles) {
+    // B operand: lane (n, g4) holds Q[row n][32s + 8 g4 .. +7]
+    bf16x8 qf[1][4];
+    const uint16_t* qrow = static_cast<const uint16_t*>(a.q) + (static_cast<int64_t>(b) * kv.num_q_heads + g * G + n) * kHeadDim;
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
+    for (int s = 0; s < 4; ++s) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (n < G) v = *reinterpret_cast<const u32x4*>(qrow + 32 * s + 8 * g4);
+      qf[0][s] = as_bf16x8(v);
+    }
+    TileRegs<FP8> regs;
+    bool first = true;
+    for (int round = 0; wave + kWaves * 4 * round < ntiles; ++round) {
+      if (round > 0) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int slot = 16 * sub + 4 * g4 + i;
-        float sc = c2;
-        vsc[sub][i] = 1.f;
-        if constexpr (FP8) {
-          sc *= __shfl(cur.ks, slot, 64);
-          vsc[sub][i] = __shfl(cur.vs, slot, 64);
+        for (int q = 0; q < 2; ++q) tok[q] = list[min(entry_of(round, q), a.max_budget - 1)];
+      }
+      // one chain for all four tiles: entries -> page ids -> row offsets.  Rows past the end of the list repeat
+      // the first row of their tile (masked later); tiles past the end resolve token 0 and are never loaded.
+      Rows rr[2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int head = __shfl(tok[q], lane & 32, 64);
+        const int e = entry_of(round, q);
+        const bool tile_there = e - (lane & 31) < j_end;
+        rr[q] = resolve_rows<FP8>(kv, b, g, e < j_end ? tok[q] : tile_there ? head : 0);
+      }
+      const int t_first = wave + kWaves * 4 * round;
+      issue_rows<FP8>(kv, rr[0], 0, regs, lane);
+      for (int k = 0; k < 4; ++k) {
+        const int ti = t_first + kWaves * k;
+        if (ti >= ntiles) break;
+        const int jb = j_begin + ti * kTileTokens;
+        const Rows& cur = (k & 2) ? rr[1] : rr[0];
+        const int half = k & 1;
+        const bool more = k < 3 && ti + kWaves < ntiles;
+        rows_to_lds<FP8, false>(regs.k, s_tile, lane);
+        f32x4 s[2][1];
+        tile_qk<1>(s_tile, qf, s, lane);
+        rows_to_lds<FP8, true>(regs.v, s_tile, lane);
+        if (more) issue_rows<FP8>(kv, ((k + 1) & 2) ? rr[1] : rr[0], (k + 1) & 1, regs, lane);
+        f32x4 vsc[2];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int slot = 16 * sub + 4 * g4 + i;
+            float sc = c2;
+            vsc[sub][i] = 1.f;
+            if constexpr (FP8) {
+              sc *= __shfl(cur.ks, 32 * half + slot, 64);
+              vsc[sub][i] = __shfl(cur.vs, 32 * half + slot, 64);
+            }
+            float v = s[sub][0][i] * sc;
+            if (jb + slot >= j_end) v = -INFINITY;
+            s[sub][0][i] = v;
+          }
         }
-        float v = s[sub][0][i] * sc;
-        if (jb + slot >= j_end) v = -INFINITY;
-        s[sub][0][i] = v;
+        float mx = fmaxf(fmaxf(fmaxf(s[0][0][0], s[0][0][1]), fmaxf(s[0][0][2], s[0][0][3])),
+                         fmaxf(fmaxf(s[1][0][0], s[1][0][1]), fmaxf(s[1][0][2], s[1][0][3])));
+        mx = max_over_groups(mx);
+        const float m_new = fmaxf(m_run, mx);              // finite: every tile has a valid row
+        const float alpha = exp2f(m_run - m_new);
+        f32x4 p0, p1;
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          p0[i] = exp2f(s[0][0][i] - m_new);
+          p1[i] = exp2f(s[1][0][i] - m_new);
+          sum += p0[i] + p1[i];
+        }
+        l_run = l_run * alpha + sum;
+        m_run = m_new;
+        if (!first) {
+#pragma unroll
+          for (int d = 0; d < 8; ++d) o[0][d] *= alpha;
+        }
+        first = false;
+        if constexpr (FP8) { p0 *= vsc[0]; p1 *= vsc[1]; }
+        bf16x8 p[1];
+        p[0] = pack_p(p0, p1);
+        tile_pv<1>(s_tile, p, o, lane);
       }
     }
-    float mx = fmaxf(fmaxf(fmaxf(s[0][0][0], s[0][0][1]), fmaxf(s[0][0][2], s[0][0][3])),
-                     fmaxf(fmaxf(s[1][0][0], s[1][0][1]), fmaxf(s[1][0][2], s[1][0][3])));
-    mx = max_over_groups(mx);
-    const float m_new = fmaxf(m_run, mx);              // finite: every tile has a valid row
-    const float alpha = exp2f(m_run - m_new);
-    f32x4 p0, p1;
-    float sum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      p0[i] = exp2f(s[0][0][i] - m_new);
-      p1[i] = exp2f(s[1][0][i] - m_new);
-      sum += p0[i] + p1[i];
-    }
-    l_run = l_run * alpha + sum;
-    m_run = m_new;
-    if (ti > 0) {
-#pragma unroll
-      for (int d = 0; d < 8; ++d) o[0][d] *= alpha;
-    }
-    if constexpr (FP8) { p0 *= vsc[0]; p1 *= vsc[1]; }
-    bf16x8 p[1];
-    p[0] = pack_p(p0, p1);
-    tile_pv<1>(s_tile, p, o, lane);
-    cur = nxt;
+    l_run = sum_over_groups(l_run);
   }
-  l_run = sum_over_groups(l_run);
 
-  if (n >= G) return;
-  const int64_t row = static_cast<int64_t>(b) * kv.num_q_heads + g * G + n;
-  if (nsplit == 1) {
-    const float inv = 1.0f / l_run;
-    uint16_t* dst = out + row * kHeadDim;
+  // combine the wavefronts of the workgroup: every one leaves (max, sum) per row and its O rows in its own tile
+  // buffer (a wavefront that had no tile leaves max = -inf, sum = 0)
+  float* part = reinterpret_cast<float*>(s_tile);          // [G][128] O, then [16] max, [16] sum
+  if (n < G) {
 #pragma unroll
-    for (int db = 0; db < 8; ++db) {
-      u32x2 pk;
-      pk.x = pack_bf16x2(o[0][db][0] * inv, o[0][db][1] * inv);
-      pk.y = pack_bf16x2(o[0][db][2] * inv, o[0][db][3] * inv);
-      *reinterpret_cast<u32x2*>(dst + 16 * db + 4 * g4) = pk;
+    for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(part + n * kHeadDim + 16 * db + 4 * g4) = o[0][db];
+    if (g4 == 0) { part[16 * kHeadDim + n] = m_run; part[16 * kHeadDim + 16 + n] = l_run; }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < G * (kHeadDim / 4); idx += kGroupThreads) {
+    const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
+    float m = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) m = fmaxf(m, reinterpret_cast<const float*>(s_tiles[w])[16 * kHeadDim + r]);
+    float l = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float* pw = reinterpret_cast<const float*>(s_tiles[w]);
+      const float wgt = exp2f(pw[16 * kHeadDim + r] - m);        // m is finite: the first wavefront always has a tile
+      l = fmaf(pw[16 * kHeadDim + 16 + r], wgt, l);
+      acc += *reinterpret_cast<const f32x4*>(pw + r * kHeadDim + 4 * d4) * wgt;
     }
-    if (a.lse && g4 == 0) a.lse[row] = (m_run + log2f(l_run)) * kLn2;
-  } else {
-    const int64_t slot = (static_cast<int64_t>(b) * kv.num_kv_heads + g) * nsplit_max + sp;
-    if (g4 == 0) { ws.part_m[slot * 16 + n] = m_run; ws.part_l[slot * 16 + n] = l_run; }
-    float* dst = ws.part_o + (slot * G + n) * kHeadDim;
-#pragma unroll
-    for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + 16 * db + 4 * g4) = o[0][db];
+    const int64_t row = static_cast<int64_t>(b) * kv.num_q_heads + g * G + r;
+    if (nspan == 1) {
+      const float inv = 1.0f / l;
+      u32x2 pk;
+      pk.x = pack_bf16x2(acc.x * inv, acc.y * inv);
+      pk.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+      *reinterpret_cast<u32x2*>(out + row * kHeadDim + 4 * d4) = pk;
+      if (d4 == 0 && a.lse) a.lse[row] = (m + log2f(l)) * kLn2;
+    } else {
+      const int64_t slot = (static_cast<int64_t>(b) * kv.num_kv_heads + g) * nspan_max + sp;
+      if (d4 == 0) { ws.part_m[slot * 16 + r] = m; ws.part_l[slot * 16 + r] = l; }
+      *reinterpret_cast<f32x4*>(ws.part_o + (slot * G + r) * kHeadDim + 4 * d4) = acc;
+    }
   }
 }
 
@@ -228,18 +282,12 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_mfma(DecodeArgs a,
   }
 }
 
-// rows of the index list per wavefront: whole 32-row tiles, as few as keeps the grid within about
-// two rounds of the wavefronts the chip holds, but no more than 8 splits per list: the merge kernel
-// walks the splits of a list one after the other (measured at 2048-row lists: 64 splits 34 us, 8 splits 9 us)
+// rows of the index list per workgroup
 int pick_split_rows(const KvView& kv, int max_budget) {
+  (void)kv;
+  (void)max_budget;
   if (options().decode_rows > 0) return options().decode_rows;
-  const int64_t pairs = static_cast<int64_t>(kv.batch) * kv.num_kv_heads;
-  const int64_t tiles = pairs * ((max_budget + kTileTokens - 1) / kTileTokens);
-  const int64_t target_waves = 8192;
-  int64_t per_wave = (tiles + target_waves - 1) / target_waves;
-  const int64_t list_tiles = (max_budget + kTileTokens - 1) / kTileTokens;
-  per_wave = std::max<int64_t>(per_wave, (list_tiles + 7) / 8);
-  return static_cast<int>(per_wave < 1 ? 1 : per_wave) * kTileTokens;
+  return kSpanRows;
 }
 
 DecWs carve(const KvView& kv, int max_budget, void* workspace, size_t* total) {
@@ -265,8 +313,8 @@ hipError_t run(const DecodeArgs& a, hipStream_t st) {
   const int nsplit = (a.max_budget + split_rows - 1) / split_rows;
   const DecWs ws = carve(kv, a.max_budget, a.workspace, nullptr);
   {
-    KernelTimer t("decode_split_mfma", st);
-    hipLaunchKernelGGL((decode_split_mfma<FP8>), dim3(nsplit, kv.num_kv_heads, kv.batch), dim3(kThreads), 0, st, a, ws, split_rows,
+    KernelTimer t("decode_span_mfma", st);
+    hipLaunchKernelGGL((decode_span_mfma<FP8>), dim3(nsplit, kv.num_kv_heads, kv.batch), dim3(kGroupThreads), 0, st, a, ws, split_rows,
                        nsplit);
   }
   if (nsplit > 1) {
@@ -332,6 +380,7 @@ hipError_t launch_decode_mfma_static(const DecodeArgs& a, hipStream_t s) {
 
 size_t decode_mfma_workspace(const KvView& kv, int max_budget) {
   if (max_budget < 1) return 0;
+  if (max_budget <= pick_split_rows(kv, max_budget)) return 0;     // one span per list: the workgroup finishes it
   size_t total = 0;
   carve(kv, max_budget, nullptr, &total);
   return total;

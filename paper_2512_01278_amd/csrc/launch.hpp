@@ -90,7 +90,7 @@ hipError_t launch_decode_mfma_static(const DecodeArgs& a, hipStream_t s);   // s
 // process-wide tuning knobs (pillar_set_option); 0 = default
 struct Options {
   int verify_waves = 0;   // wavefronts per compute unit of the two verification passes
-  int decode_rows = 0;    // rows of the index list per wavefront of the draft kernel
+  int decode_rows = 0;    // rows of the index list per workgroup of the draft kernel
 };
 Options& options();
 
