@@ -40,7 +40,7 @@ from __future__ import annotations
 import numpy as np
 
 __all__ = ["decode_tensor", "e4m3_table", "gather_request", "verify_attn",
-           "select_topk", "sparse_decode", "run_all"]
+           "select_topk", "sparse_decode", "run_all", "mixed_step"]
 
 
 # ---------------------------------------------------------------------------
@@ -209,6 +209,32 @@ def run_all(w):
     d_out, d_lse = sparse_decode(w, idx, counts)
     return dict(out=out, lse=lse, scores=scores, indices=idx, counts=counts,
                 draft_out=d_out, draft_lse=d_lse)
+
+
+def mixed_step(w, verify_ids, draft_ids, indices, counts):
+    """One iteration of a unified batch (Section 4.2, "Unified Batch Scheduler" and "Fused Sparse and Full
+    Attention"): in the same iteration some requests are in their verification phase and the others in a draft
+    phase.  Every request in `verify_ids` runs the verification attention on its k+1 queries and then selects
+    its critical tokens anew (its rows of `indices` / `counts` are replaced); every request in `draft_ids` runs
+    one sparse draft step on the lists it already has.  Nothing else is touched: the result is, request by
+    request, what verify_attn + select_topk or sparse_decode give for that request alone.
+
+    Returns a dict: out, lse, scores (verification; zeros for other requests), indices, counts (updated copies),
+    draft_out, draft_lse (zeros / -inf for other requests).
+    """
+    verify_ids = [int(b) for b in verify_ids]
+    draft_ids = [int(b) for b in draft_ids]
+    assert not set(verify_ids) & set(draft_ids), "a request is in one phase at a time"
+    out, lse, scores = verify_attn(w, requests=verify_ids)
+    idx = np.array(indices, dtype=np.int32, copy=True)
+    cnt = np.array(counts, dtype=np.int32, copy=True)
+    if verify_ids:
+        sub = np.asarray(verify_ids)
+        new_idx, new_cnt = select_topk(scores[sub], w.seq_lens[sub], w.budgets[sub], max_budget=idx.shape[2])
+        idx[sub], cnt[sub] = new_idx, new_cnt
+    # the draft requests use the lists they came with (a request is never in both sets)
+    d_out, d_lse = sparse_decode(w, indices, counts, requests=draft_ids)
+    return dict(out=out, lse=lse, scores=scores, indices=idx, counts=cnt, draft_out=d_out, draft_lse=d_lse)
 
 
 # ---------------------------------------------------------------------------

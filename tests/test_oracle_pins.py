@@ -403,3 +403,44 @@ def test_per_request_speculative_lengths_reduce_to_uniform_runs():
     d_out, d_lse = oracle.sparse_decode(wd, idx, cnt, requests=[b])
     assert np.allclose(d_out[b], out[b, 0], atol=1e-12) and np.allclose(d_lse[b], lse[b, 0], atol=1e-12)
 
+
+
+# ---------------------------------------------------- mixed draft / verify batch ----
+def test_mixed_step_reduces_to_the_two_pure_batches():
+    """A unified batch is, request by request, one of the two pure batches: everything verifying equals
+    verify_attn + select_topk, everything drafting equals sparse_decode, and a mixed batch equals, for each
+    request, the pure result of its phase computed for that request alone (both pure functions are pinned
+    above); requests of the other phase keep their lists and get no output."""
+    w = tiny(41, B=5, spec_k=2, Hq=4, Hkv=2, D=16, seq_lens=[9, 40, 17, 33, 5], budgets=[3, 8, 4, 6, 2],
+             q_dtype="bf16", kv_dtype="bf16")
+    rng = np.random.default_rng(3)
+    old_idx = np.full((w.B, w.Hkv, 8), -1, dtype=np.int32)
+    old_cnt = np.array([2, 5, 0, 6, 1], dtype=np.int32)
+    for b in range(w.B):
+        for g in range(w.Hkv):
+            old_idx[b, g, :old_cnt[b]] = np.sort(rng.choice(int(w.seq_lens[b]), size=old_cnt[b], replace=False))
+    full = oracle.run_all(w)
+    allv = oracle.mixed_step(w, range(w.B), [], old_idx, old_cnt)
+    np.testing.assert_array_equal(allv["out"], full["out"])
+    np.testing.assert_array_equal(allv["scores"], full["scores"])
+    np.testing.assert_array_equal(allv["indices"][:, :, :full["indices"].shape[2]], full["indices"])
+    np.testing.assert_array_equal(allv["counts"], full["counts"])
+    want_d, want_dl = oracle.sparse_decode(w, old_idx, old_cnt)
+    alld = oracle.mixed_step(w, [], range(w.B), old_idx, old_cnt)
+    np.testing.assert_array_equal(alld["draft_out"], want_d)
+    np.testing.assert_array_equal(alld["indices"], old_idx)
+    ver, dra = [3, 0], [4, 1, 2]
+    mix = oracle.mixed_step(w, ver, dra, old_idx, old_cnt)
+    for b in ver:
+        np.testing.assert_array_equal(mix["out"][b], full["out"][b])
+        np.testing.assert_array_equal(mix["lse"][b], full["lse"][b])
+        kk = int(full["counts"][b])
+        assert mix["counts"][b] == kk and np.array_equal(mix["indices"][b, :, :kk], full["indices"][b, :, :kk])
+        assert np.all(mix["draft_out"][b] == 0)
+    for b in dra:
+        np.testing.assert_array_equal(mix["draft_out"][b], want_d[b])
+        np.testing.assert_array_equal(mix["draft_lse"][b], want_dl[b])
+        assert mix["counts"][b] == old_cnt[b] and np.array_equal(mix["indices"][b], old_idx[b])
+        assert np.all(mix["out"][b] == 0) and np.all(mix["scores"][b] == 0)
+    with pytest.raises(AssertionError):
+        oracle.mixed_step(w, [1], [1], old_idx, old_cnt)
