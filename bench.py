@@ -74,6 +74,95 @@ def recorded_traffic(config: int):
     return None
 
 
+def mixed_mode(args, w, run, gen, pa, torch) -> dict:
+    """A unified batch of paper Section 4.2 on the same workload: every (k+1)-th request is in its verification
+    phase, the others draft on the lists of their last verification.  Times pillar_mixed_step (one grid for both
+    phases) against the same work as two calls on one stream and as two calls on two streams."""
+    import numpy as np
+    dev = run.dev
+    ver = [b for b in range(w.B) if b % w.n_q == 0]
+    dra = [b for b in range(w.B) if b % w.n_q != 0]
+    v_ids = torch.tensor(ver, dtype=torch.int32, device=dev)
+    d_ids = torch.tensor(dra, dtype=torch.int32, device=dev)
+    run.verify_select()                                   # every request owns a list before the timed steps
+    torch.cuda.synchronize()
+    kv, k = run.dw.kv, w.spec_k
+
+    def call(v, d, stream=None):
+        pa.pillar_mixed_step(kv, v, d, run.dw.q, k, run.out, run.lse, run.scores, run.dw.budgets, run.max_budget, run.indices,
+                             run.counts, run.dw.q_draft, run.d_out, run.d_lse, run.workspace, stream=stream)
+
+    side = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+
+    def fused():
+        call(v_ids, d_ids)
+
+    def sequential():
+        call(v_ids, None)
+        call(None, d_ids)
+
+    def two_streams():
+        side.wait_stream(main)
+        call(v_ids, None)
+        with torch.cuda.stream(side):
+            call(None, d_ids, stream=side)
+        main.wait_stream(side)
+
+    def time_us(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        per = []
+        for _ in range(args.steps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(main)
+            fn()
+            e1.record(main)
+            per.append((e0, e1))
+        torch.cuda.synchronize()
+        t = sorted(a.elapsed_time(b) * 1e3 for a, b in per)
+        return t[len(t) // 2], sum(t) / len(t)
+
+    res = {}
+    for name, fn in (("fused", fused), ("sequential", sequential), ("two_streams", two_streams)):
+        med, mean = time_us(fn)
+        res[name] = {"median_us": round(med, 2), "mean_us": round(mean, 2)}
+    pa.pillar_profile_reset()
+    pa.pillar_profile_enable(True)
+    for _ in range(args.steps):
+        fused()
+    torch.cuda.synchronize()
+    pa.pillar_profile_enable(False)
+    prof = pa.pillar_profile_read()
+    kern = {k_: {"launches": n, "avg_us": round(ms * 1e3 / max(n, 1), 2)} for k_, (n, ms) in prof.items()}
+    tok_v = int(w.seq_lens[ver].astype(np.int64).sum())
+    e = w.kv_elem_bytes()
+    vb = tok_v * w.Hkv * (2 * w.D * e + 4) + 2 * len(ver) * w.n_q * w.Hq * w.D * w.q_elem_bytes()
+    rows_d = int(np.minimum(w.budgets[dra], w.seq_lens[dra]).astype(np.int64).sum()) * w.Hkv
+    db = rows_d * (2 * w.D * e + 4) + 2 * len(dra) * w.Hq * w.D * w.q_elem_bytes()
+    us = res["fused"]["median_us"]
+    gbps = (vb + db) / (us * 1e-6) / 1e9
+    return {
+        "metric": METRIC, "value": us, "unit": "µs/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us * 1e-3, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.kv_dtype == "bf16" else w.kv_dtype, "data": "synthetic",
+        "config": {"workload": f"config {args.config}, unified batch: {len(ver)} of {w.B} requests verify (every {w.n_q}th), "
+                               f"{len(dra)} draft: {gen.CONFIGS[args.config]}",
+                   "calls": "pillar_mixed_step", "batch": w.B, "verifying": len(ver), "drafting": len(dra)},
+        "mixed": {**res, "fused_vs_sequential": round(res["sequential"]["median_us"] / us, 3),
+                  "fused_vs_two_streams": round(res["two_streams"]["median_us"] / us, 3),
+                  "note": "per-step HIP-event times on the launch stream, median of the timed steps; sequential = "
+                          "pillar_mixed_step with only the verifying list, then with only the drafting list"},
+        "algorithmic_bytes": {"verify": vb, "draft": db},
+        "kernels": kern,
+        "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": "whole unified step (all kernels of pillar_mixed_step)", "avg_us": us,
+                     "algorithmic_bytes": vb + db},
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,6 +176,9 @@ def main() -> int:
     ap.add_argument("--index-source", choices=["pillar", "window"], default="pillar",
                     help="window: the sliding-window draft the paper compares against -- verification without the "
                          "statistic, a static list of 4 sinks + the most recent tokens with the same budgets, draft")
+    ap.add_argument("--mixed", action="store_true",
+                    help="a unified draft / verify batch (paper Section 4.2): every (k+1)-th request verifies, the others "
+                         "draft; pillar_mixed_step against the same work as two calls and on two streams")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB -> 1 GiB float copy kernel (for scaling rocprofv3's "
@@ -110,6 +202,9 @@ def main() -> int:
           file=sys.stderr, flush=True)
     run = GpuRun(w)
     torch.cuda.synchronize()
+    if args.mixed:
+        print(json.dumps(mixed_mode(args, w, run, gen, pa, torch), ensure_ascii=False))
+        return 0
     stream = torch.cuda.current_stream()
 
     def step():

@@ -191,6 +191,35 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
                          const int32_t* counts, int32_t max_budget, void* out, float* lse,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* One iteration of a unified batch (Section 4.2: "Unified Batch Scheduler" and
+ * "Fused Sparse and Full Attention"): in the same iteration the requests listed
+ * in verify_ids are in their verification phase and those in draft_ids in a
+ * draft phase.  Per request the results are those of pillar_verify_select
+ * (verify_ids) or pillar_sparse_decode (draft_ids) for that request alone:
+ *   verify_ids  device [n_verify], draft_ids device [n_draft]: request indices
+ *               in 0..batch-1, no request in both, none twice; the counts are
+ *               host values (the scheduler that forms the batch knows them).
+ *   q_verify / out_verify / lse_verify / scores, q_draft / out_draft / lse_draft,
+ *   budgets / indices / counts: the full-batch tensors of the two calls, indexed
+ *               by request id.  Only the rows of listed requests are read or
+ *               written: a verifying request gets new out / lse / scores rows
+ *               and a new index list and count; a drafting request reads its
+ *               current list and gets out_draft / lse_draft rows.
+ * Where the shapes allow it (up to 32 query rows per KV head) both phases run
+ * in ONE grid: the workgroups of the streaming verification pass and those of
+ * the draft step are dispatched to their code path on the chip; otherwise the
+ * draft kernel is launched right after the verification's.  Either list may
+ * be empty.  Matrix-core shapes only (bf16 queries, bf16 or fp8 KV, head_dim
+ * 128, pages of >= 16 tokens, rows of up to 32768 tokens, flags 0); anything
+ * else returns PILLAR_EUNSUPPORTED.  Workspace: pillar_workspace_bytes(). */
+int pillar_mixed_step(const pillar_kv_t* kv, const int32_t* verify_ids, int32_t n_verify,
+                      const int32_t* draft_ids, int32_t n_draft,
+                      const void* q_verify, int32_t spec_len_k, void* out_verify, float* lse_verify,
+                      float* scores, int64_t score_stride,
+                      const int32_t* budgets, int32_t max_budget, int32_t* indices, int32_t* counts,
+                      const void* q_draft, void* out_draft, float* lse_draft,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* pillar_sparse_decode for callers that can hand over no workspace and must
  * not cause an allocation: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments, same kernels and the same

@@ -24,7 +24,7 @@ PILLAR_FLAG_EXACT_SCORES, PILLAR_FLAG_GENERIC_KERNELS = 1, 2
 DTYPE_CODE = {"f32": PILLAR_F32, "bf16": PILLAR_BF16, "fp8_e4m3": PILLAR_FP8_E4M3}
 
 EXPORTS = ("pillar_version", "pillar_status_string", "pillar_workspace_bytes", "pillar_verify_attn",
-           "pillar_verify_select", "pillar_verify_hetero", "pillar_select_topk", "pillar_sparse_decode", "pillar_sparse_decode_static", "pillar_window_indices",
+           "pillar_verify_select", "pillar_verify_hetero", "pillar_mixed_step", "pillar_select_topk", "pillar_sparse_decode", "pillar_sparse_decode_static", "pillar_window_indices",
            "pillar_extend_indices", "pillar_append_kv", "pillar_profile_enable", "pillar_profile_reset",
            "pillar_profile_read", "pillar_set_option")
 
@@ -81,6 +81,10 @@ def load() -> C.CDLL:
     lib.pillar_verify_hetero.argtypes = [C.POINTER(pillar_kv_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.pillar_mixed_step.restype = C.c_int
+    lib.pillar_mixed_step.argtypes = [C.POINTER(pillar_kv_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.pillar_select_topk.restype = C.c_int
     lib.pillar_select_topk.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                        C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
@@ -213,6 +217,21 @@ def pillar_verify_hetero(kv: KvCache, q: torch.Tensor, spec_len_max: int, spec_l
                                      _ptr(scores), stride, _ptr(budgets), max_budget, _ptr(indices), _ptr(counts),
                                      workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "pillar_verify_hetero")
+
+
+def pillar_mixed_step(kv: KvCache, verify_ids: Optional[torch.Tensor], draft_ids: Optional[torch.Tensor], q_verify: torch.Tensor,
+                      spec_len_k: int, out_verify: torch.Tensor, lse_verify: Optional[torch.Tensor], scores: Optional[torch.Tensor],
+                      budgets: torch.Tensor, max_budget: int, indices: torch.Tensor, counts: torch.Tensor, q_draft: torch.Tensor,
+                      out_draft: torch.Tensor, lse_draft: Optional[torch.Tensor], workspace: torch.Tensor, stream=None) -> None:
+    s = kv.c_struct()
+    stride = scores.stride(1) if scores is not None else 0
+    nv = 0 if verify_ids is None else verify_ids.numel()
+    nd = 0 if draft_ids is None else draft_ids.numel()
+    rc = load().pillar_mixed_step(C.byref(s), _ptr(verify_ids), nv, _ptr(draft_ids), nd, q_verify.data_ptr(), spec_len_k,
+                                  out_verify.data_ptr(), _ptr(lse_verify), _ptr(scores), stride, budgets.data_ptr(), max_budget,
+                                  indices.data_ptr(), counts.data_ptr(), q_draft.data_ptr(), out_draft.data_ptr(), _ptr(lse_draft),
+                                  workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "pillar_mixed_step")
 
 
 def pillar_select_topk(scores: torch.Tensor, seq_lens: torch.Tensor, budgets: torch.Tensor,

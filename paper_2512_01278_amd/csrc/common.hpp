@@ -21,11 +21,17 @@ struct KvView {
   const float* v_scale;
   const int32_t* block_table;
   const int32_t* seq_lens;
+  const int32_t* req_ids;      // null: slot i of this launch is request i; else request req_ids[i] (batch = number of slots)
   int64_t stride_page, stride_head, stride_slot;
   int32_t batch, num_q_heads, num_kv_heads, head_dim, page_size, page_shift;
   int32_t block_table_stride, max_seq_len;
   float sm_scale;
 };
+
+// A launch may cover a subset of the requests (a unified batch: some verify while the others draft).  Work is
+// divided over the slots 0 .. batch-1 of the launch; everything a request owns (its row of the block table, its
+// length, its queries, outputs, scores and index lists) is indexed by the request id of the slot.
+__device__ __forceinline__ int request_of(const KvView& kv, int slot) { return kv.req_ids ? kv.req_ids[slot] : slot; }
 
 // ---- storage formats -------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {

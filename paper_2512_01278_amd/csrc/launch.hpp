@@ -55,6 +55,13 @@ struct DecodeArgs {
   void* workspace;
 };
 
+// split partials of the draft step (decode_mfma.hip carves them out of the workspace)
+struct DecWs {
+  float* part_m;   // [B][Hkv][nsplit][16]  log2 domain
+  float* part_l;   // [B][Hkv][nsplit][16]
+  float* part_o;   // [B][Hkv][nsplit][G][128]
+};
+
 struct TopkArgs {
   const float* scores;
   int64_t score_stride;
@@ -79,11 +86,17 @@ hipError_t launch_extend_indices(int32_t* indices, int32_t* counts, const int32_
 // matrix-core paths (bf16 queries, bf16 / fp8 KV, head_dim 128, pages >= 16)
 bool verify_range_supported(const VerifyArgs& a);
 size_t verify_range_workspace(const KvView& kv, int n_q);
-hipError_t launch_verify_range(const VerifyArgs& a, hipStream_t s);
+// `fused_draft` (optional): one draft step of other requests that shares the grid of the streaming pass; only
+// where verify_fuses_draft(a) holds.  The caller still owes nothing: the draft's merge launch is included.
+hipError_t launch_verify_range(const VerifyArgs& a, hipStream_t s, const DecodeArgs* fused_draft = nullptr);
+bool verify_fuses_draft(const VerifyArgs& a);
 bool verify_select_fused(const VerifyArgs& a);          // a.select can be served by the finish kernel itself
 bool decode_mfma_supported(const DecodeArgs& a);
 size_t decode_mfma_workspace(const KvView& kv, int max_budget);
 hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s);
+int decode_span_rows(const KvView& kv, int max_budget);   // rows of an index list one workgroup takes
+DecWs decode_carve(const KvView& kv, int max_budget, void* workspace);
+hipError_t launch_decode_merge(const DecodeArgs& a, hipStream_t s);          // combines the spans of lists longer than one
 size_t decode_static_scratch_bytes();                     // size of the library's own scratch array
 hipError_t launch_decode_mfma_static(const DecodeArgs& a, hipStream_t s);   // same kernels, partials in that array
 

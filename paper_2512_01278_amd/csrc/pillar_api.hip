@@ -103,6 +103,7 @@ KvView make_view(const pillar_kv_t* kv) {
   v.v_scale = kv->v_scale;
   v.block_table = kv->block_table;
   v.seq_lens = kv->seq_lens;
+  v.req_ids = nullptr;
   v.stride_page = kv->stride_page;
   v.stride_head = kv->stride_head;
   v.stride_slot = kv->stride_slot;
@@ -152,9 +153,15 @@ size_t scratch_scores_bytes(const KvView& v) {
   return static_cast<size_t>(v.batch) * v.num_kv_heads * scratch_score_stride(v) * sizeof(float);
 }
 
+size_t draft_region_offset(const KvView& v, int n_q) {
+  return align_up(align_up(verify_workspace(v, n_q), 256) + scratch_scores_bytes(v), 256);
+}
+
+// req_ids / n_req (optional): the call covers only these requests (device list of request indices); draft (optional): one
+// draft step of other requests to run in the same grid where the kernels allow it, else right after.
 int verify_common(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, const int32_t* spec_lens, void* out, float* lse,
                   float* scores, int64_t score_stride, const SelectOut* select, void* workspace, size_t workspace_bytes,
-                  void* hip_stream) {
+                  void* hip_stream, const int32_t* req_ids = nullptr, int32_t n_req = 0, const DecodeArgs* draft = nullptr) {
   int rc = check_kv(kv);
   if (rc != PILLAR_OK) return rc;
   rc = check_spec(kv, spec_len_k);
@@ -163,6 +170,10 @@ int verify_common(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, cons
   if (scores && score_stride < kv->max_seq_len) return PILLAR_EINVAL;
   VerifyArgs a;
   a.kv = make_view(kv);
+  if (req_ids) {
+    a.kv.req_ids = req_ids;
+    a.kv.batch = n_req;
+  }
   a.q = q;
   a.out = out;
   a.lse = lse;
@@ -184,6 +195,7 @@ int verify_common(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, cons
   const hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (select && !(!generic && verify_select_fused(a))) {
     // two steps: the statistic goes through memory (the caller's buffer, or scratch behind the stage workspace)
+    if (req_ids) return PILLAR_EUNSUPPORTED;      // (the stand-alone Top-K kernel knows no request lists)
     a.select = nullptr;
     if (!a.scores) {
       a.scores = reinterpret_cast<float*>(static_cast<char*>(workspace) + align_up(stage_ws, 256));
@@ -205,8 +217,14 @@ int verify_common(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, cons
     return launch_topk(t, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
   }
   hipError_t e;
-  if (!generic && verify_range_supported(a)) e = launch_verify_range(a, st);
-  else e = launch_verify_generic(a, st);
+  if (!generic && verify_range_supported(a)) {
+    if (draft && verify_fuses_draft(a)) return launch_verify_range(a, st, draft) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+    e = launch_verify_range(a, st);
+  } else {
+    e = launch_verify_generic(a, st);
+  }
+  if (e != hipSuccess) return PILLAR_EHIP;
+  if (draft) e = launch_decode_mfma(*draft, st);
   return e == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
 }
 
@@ -231,10 +249,9 @@ const char* pillar_status_string(int status) {
 size_t pillar_workspace_bytes(const pillar_kv_t* kv, int32_t spec_len_k, int32_t max_budget) {
   if (check_kv(kv) != PILLAR_OK || check_spec(kv, spec_len_k) != PILLAR_OK || max_budget < 0) return 0;
   const KvView v = make_view(kv);
-  size_t need = verify_workspace(v, spec_len_k + 1);
-  need = align_up(need, 256) + scratch_scores_bytes(v);      // scratch for pillar_verify_select's two-step fallback
-  const size_t dec = (v.head_dim == 128) ? decode_mfma_workspace(v, max_budget) : 0;
-  if (dec > need) need = dec;
+  // [verification | scores of pillar_verify_select's two-step fallback | draft partials]: the draft region is its
+  // own so that a unified batch (pillar_mixed_step) can run both at once
+  const size_t need = draft_region_offset(v, spec_len_k + 1) + ((v.head_dim == 128) ? decode_mfma_workspace(v, max_budget) : 0);
   return need < 256 ? 256 : need;
 }
 
@@ -321,6 +338,66 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
     return launch_decode_mfma(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
   }
   return launch_decode_generic(a, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+}
+
+int pillar_mixed_step(const pillar_kv_t* kv, const int32_t* verify_ids, int32_t n_verify, const int32_t* draft_ids,
+                      int32_t n_draft, const void* q_verify, int32_t spec_len_k, void* out_verify, float* lse_verify,
+                      float* scores, int64_t score_stride, const int32_t* budgets, int32_t max_budget, int32_t* indices,
+                      int32_t* counts, const void* q_draft, void* out_draft, float* lse_draft, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  int rc = check_kv(kv);
+  if (rc != PILLAR_OK) return rc;
+  rc = check_spec(kv, spec_len_k);
+  if (rc != PILLAR_OK) return rc;
+  if (n_verify < 0 || n_draft < 0 || n_verify > kv->batch || n_draft > kv->batch) return PILLAR_EINVAL;
+  if ((n_verify > 0 && (!verify_ids || !q_verify || !out_verify)) || (n_draft > 0 && (!draft_ids || !q_draft || !out_draft)))
+    return PILLAR_EINVAL;
+  if (!budgets || !indices || !counts || max_budget < 1) return PILLAR_EINVAL;
+  if (kv->flags != 0) return PILLAR_EUNSUPPORTED;            // matrix-core kernels, default statistic only
+  const KvView full = make_view(kv);
+  const size_t dec_off = draft_region_offset(full, spec_len_k + 1);
+  rc = check_workspace(workspace, workspace_bytes, dec_off + decode_mfma_workspace(full, max_budget));
+  if (rc != PILLAR_OK) return rc;
+  const hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  DecodeArgs d;
+  d.kv = full;
+  d.kv.req_ids = draft_ids;
+  d.kv.batch = n_draft;
+  d.q = q_draft;
+  d.indices = indices;
+  d.counts = counts;
+  d.max_budget = max_budget;
+  d.out = out_draft;
+  d.lse = lse_draft;
+  d.q_dtype = kv->q_dtype;
+  d.kv_dtype = kv->kv_dtype;
+  d.workspace = static_cast<char*>(workspace) + dec_off;
+  if (n_draft > 0 && !decode_mfma_supported(d)) return PILLAR_EUNSUPPORTED;
+  if (n_verify == 0) {
+    if (n_draft == 0) return PILLAR_OK;
+    return launch_decode_mfma(d, st) == hipSuccess ? PILLAR_OK : PILLAR_EHIP;
+  }
+  {
+    VerifyArgs probe;                            // the shapes the matrix-core verification takes
+    probe.kv = full;
+    probe.q = q_verify;
+    probe.out = out_verify;
+    probe.lse = lse_verify;
+    probe.scores = scores;
+    probe.score_stride = score_stride;
+    probe.n_q = spec_len_k + 1;
+    probe.q_dtype = kv->q_dtype;
+    probe.kv_dtype = kv->kv_dtype;
+    probe.workspace = workspace;
+    if (!verify_range_supported(probe)) return PILLAR_EUNSUPPORTED;
+  }
+  SelectOut sel;
+  sel.budgets = budgets;
+  sel.max_budget = max_budget;
+  sel.indices = indices;
+  sel.counts = counts;
+  return verify_common(kv, q_verify, spec_len_k, nullptr, out_verify, lse_verify, scores, score_stride, &sel, workspace,
+                       workspace_bytes, hip_stream, verify_ids, n_verify, n_draft > 0 ? &d : nullptr);
 }
 
 int pillar_sparse_decode_static(const pillar_kv_t* kv, const void* q, const int32_t* indices, const int32_t* counts,

@@ -40,6 +40,7 @@
 #include "mfma_tile.hpp"
 #include "topk_core.hpp"
 #include "verify_stream.hpp"
+#include "decode_span.hpp"
 
 namespace pillar {
 namespace {
@@ -66,7 +67,9 @@ struct RangeWs {
 __host__ __device__ inline int tiles_of_len(int len) { return (len + kTileTokens - 1) / kTileTokens; }
 
 // query positions of request b: all n_q slots, or as many as the request speculates
-__device__ __forceinline__ int queries_of(const RangeWs& ws, int b, int n_q) { return ws.spec_lens ? min(ws.spec_lens[b] + 1, n_q) : n_q; }
+__device__ __forceinline__ int queries_of(const KvView& kv, const RangeWs& ws, int b, int n_q) {
+  return ws.spec_lens ? min(ws.spec_lens[request_of(kv, b)] + 1, n_q) : n_q;
+}
 
 // first unit of range w, and the range a unit falls in
 __device__ __forceinline__ int range_begin(int w, int total, int n) { return static_cast<int>(static_cast<int64_t>(w) * total / n); }
@@ -84,7 +87,7 @@ __global__ __launch_bounds__(1024) void range_plan(KvView kv, RangeWs ws) {
   __syncthreads();
   for (int b0 = 0; b0 < kv.batch; b0 += 1024) {
     const int b = b0 + threadIdx.x;
-    const int mine = b < kv.batch ? tiles_of_len(kv.seq_lens[b]) * kv.num_kv_heads : 0;
+    const int mine = b < kv.batch ? tiles_of_len(kv.seq_lens[request_of(kv, b)]) * kv.num_kv_heads : 0;
     scan[threadIdx.x] = mine;
     __syncthreads();
     for (int o = 1; o < 1024; o <<= 1) {
@@ -106,7 +109,7 @@ __global__ __launch_bounds__(1024) void range_plan(KvView kv, RangeWs ws) {
   if (kv.batch <= 1024) {
     __syncthreads();
     const int b = threadIdx.x;
-    const int len = b < kv.batch ? kv.seq_lens[b] : 0;
+    const int len = b < kv.batch ? kv.seq_lens[request_of(kv, b)] : 0;
     scan[threadIdx.x] = len;
     __syncthreads();
     if (b < kv.batch) {
@@ -125,7 +128,8 @@ __global__ __launch_bounds__(1024) void range_plan(KvView kv, RangeWs ws) {
 // ------------------------------------------------------------- helpers ------
 // One stretch of one pair inside one range.
 struct Segment {
-  int b, g, L, tiles, tile0, tile1, pair, slot;
+  int b, g, L, tiles, tile0, tile1, pair, slot;   // b: slot of the request in this launch
+  int rq;                                          // the request's id: index into everything the request owns
 };
 
 // request whose units contain `unit`: two rounds of 64-way search, the prefix table stays in L2
@@ -204,7 +208,7 @@ __device__ __forceinline__ void load_q_regs(const KvView& kv, const uint16_t* q,
   for (int rb = 0; rb < RB; ++rb) {
     const int r = 16 * rb + n;
     const int i = r / G, hg = r - i * G;
-    const uint16_t* row = q + ((static_cast<int64_t>(sg.b) * n_q + i) * kv.num_q_heads + sg.g * G + hg) * kHeadDim;
+    const uint16_t* row = q + ((static_cast<int64_t>(sg.rq) * n_q + i) * kv.num_q_heads + sg.g * G + hg) * kHeadDim;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       u32x4 v = {0u, 0u, 0u, 0u};
@@ -238,13 +242,13 @@ struct Cursor {
 __device__ __forceinline__ int load_window(const KvView& kv, int b, int win, int lane) {
   // entries past the last page of the request are never used as addresses (issue_tile clamps), so
   // it is enough to stay inside the table row
-  return kv.block_table[static_cast<int64_t>(b) * kv.block_table_stride + min(win * kWindowPages + lane, kv.block_table_stride - 1)];
+  return kv.block_table[static_cast<int64_t>(request_of(kv, b)) * kv.block_table_stride + min(win * kWindowPages + lane, kv.block_table_stride - 1)];
 }
 
 __device__ __forceinline__ void prefetch_following(const KvView& kv, Cursor& c, int lane) {
   int nb = c.sg.b + (c.sg.g + 1 == kv.num_kv_heads ? 1 : 0);
   nb = min(nb, kv.batch - 1);                  // past the last request nothing of this is used
-  c.len_next = kv.seq_lens[nb];
+  c.len_next = kv.seq_lens[request_of(kv, nb)];
   c.pg_next = load_window(kv, nb, 0, lane);
 }
 
@@ -258,13 +262,14 @@ __device__ __forceinline__ Segment uniform(const Segment& s) {
   u.tile1 = __builtin_amdgcn_readfirstlane(s.tile1);
   u.pair = __builtin_amdgcn_readfirstlane(s.pair);
   u.slot = __builtin_amdgcn_readfirstlane(s.slot);
+  u.rq = __builtin_amdgcn_readfirstlane(s.rq);
   return u;
 }
 
-__device__ __forceinline__ Cursor open_cursor(const KvView& kv, const RangeWs& ws, int lane) {
+__device__ __forceinline__ Cursor open_cursor(const KvView& kv, const RangeWs& ws, int w, int lane) {
   Cursor c;
   const int total = ws.ctrl[0];
-  c.w = blockIdx.x;
+  c.w = w;
   c.unit = range_begin(c.w, total, ws.n_ranges);
   c.end = range_begin(c.w + 1, total, ws.n_ranges);
   c.live = c.unit < c.end;
@@ -276,7 +281,8 @@ __device__ __forceinline__ Cursor open_cursor(const KvView& kv, const RangeWs& w
   if (!c.live) return c;
   Segment sg;
   sg.b = find_request(ws, kv.batch, c.unit, lane);
-  sg.L = __builtin_amdgcn_readfirstlane(kv.seq_lens[sg.b]);
+  sg.rq = __builtin_amdgcn_readfirstlane(request_of(kv, sg.b));
+  sg.L = __builtin_amdgcn_readfirstlane(kv.seq_lens[sg.rq]);
   sg.tiles = tiles_of_len(sg.L);
   const int rel = c.unit - __builtin_amdgcn_readfirstlane(ws.ureq[sg.b]);
   sg.g = rel / sg.tiles;
@@ -313,6 +319,7 @@ __device__ __forceinline__ void advance_cursor(const KvView& kv, Cursor& c, int 
     sg.tile1 = min(sg.tiles, c.end - c.unit);
     sg.pair = sg.b * kv.num_kv_heads + sg.g;
     sg.slot = sg.pair + c.w;
+    sg.rq = request_of(kv, sg.b);
     c.sg = uniform(sg);
     c.tile = 0;
     c.pw.win = 0;
@@ -372,7 +379,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_lse_range(KvView kv, const
   const float c2 = kv.sm_scale * kLog2e;
   const LaneGeom<FP8> geo = lane_geom<FP8>(kv, lane);
   constexpr int kLoads = TileRegs<FP8>::kLoads;
-  Cursor cur = open_cursor(kv, ws, lane);
+  Cursor cur = open_cursor(kv, ws, blockIdx.x, lane);
   if (!cur.live) return;
   // K tiles travel two deep: even tiles through ra, odd tiles through rb_
   u32x4 ra[kLoads], rb_[kLoads], unused[kLoads];
@@ -456,7 +463,8 @@ __global__ __launch_bounds__(256) void verify_lse_combine_range(KvView kv, int n
   const int b = pair / kv.num_kv_heads, g = pair - b * kv.num_kv_heads;
   const int G = kv.num_q_heads / kv.num_kv_heads;
   const int total = ws.ctrl[0];
-  const int tiles = tiles_of_len(kv.seq_lens[b]);
+  const int rq = request_of(kv, b);
+  const int tiles = tiles_of_len(kv.seq_lens[rq]);
   const int u0 = ws.ureq[b] + g * tiles;
   const int w0 = range_of(u0, total, ws.n_ranges), w1 = range_of(u0 + tiles - 1, total, ws.n_ranges);
   const float* pm = ws.part_m + static_cast<int64_t>(pair + w0) * rows + row;
@@ -473,13 +481,13 @@ __global__ __launch_bounds__(256) void verify_lse_combine_range(KvView kv, int n
   }
   // rows beyond the request's R, and rows that see no token at all (a context shorter than the request's
   // queries), get +inf so that their probabilities vanish where the log-sum-exp is applied
-  const int Rb = queries_of(ws, b, n_q) * G;
+  const int Rb = queries_of(kv, ws, b, n_q) * G;
   const bool live = row < Rb && l > 0.f;
   const float v = live ? m + log2f(l) : INFINITY;
   ws.lse2[idx] = v;
   if (lse_out && row < Rb) {
     const int i = row / G, hg = row - i * G;
-    lse_out[(static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg] = live ? v * kLn2 : -INFINITY;
+    lse_out[(static_cast<int64_t>(rq) * n_q + i) * kv.num_q_heads + g * G + hg] = live ? v * kLn2 : -INFINITY;
   }
 }
 
@@ -499,7 +507,7 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_score_range(
   const LaneGeom<FP8> geo = lane_geom<FP8>(kv, lane);
   constexpr int kLoads = TileRegs<FP8>::kLoads;
   constexpr int kQIters = ((RB * 16 + 1) * 16 + kThreads - 1) / kThreads;
-  Cursor cur = open_cursor(kv, ws, lane);
+  Cursor cur = open_cursor(kv, ws, blockIdx.x, lane);
   if (!cur.live) return;
   u32x4 rk[kLoads], rv[kLoads];
   Flight f = issue_next<FP8, true>(kv, cur, geo, lane, rk, rv);
@@ -516,7 +524,7 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_score_range(
       if (r >= R) continue;
       if (whole) {
         const int i = r / G, hg = r - i * G;
-        uint16_t* dst = out + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim;
+        uint16_t* dst = out + ((static_cast<int64_t>(cs.rq) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim;
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
           u32x2 pk;
@@ -545,7 +553,7 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_score_range(
           u32x4 v = {0u, 0u, 0u, 0u};
           if (r < R) {
             const int i = r / G, hg = r - i * G;
-            v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim + 8 * c);
+            v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(cs.rq) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim + 8 * c);
           }
           qtmp[j] = v;
         }
@@ -557,7 +565,7 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_score_range(
       }
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) lse2[rb] = ws.lse2[static_cast<int64_t>(cs.pair) * (RB * 16) + 16 * rb + n];
-      sdst = scores + (static_cast<int64_t>(cs.b) * kv.num_kv_heads + cs.g) * score_stride;
+      sdst = scores + (static_cast<int64_t>(cs.rq) * kv.num_kv_heads + cs.g) * score_stride;
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -627,7 +635,8 @@ __global__ __launch_bounds__(256) void verify_o_merge_range(KvView kv, int n_q, 
   const int G = kv.num_q_heads / kv.num_kv_heads;
   const int R = n_q * G;
   const int total = ws.ctrl[0];
-  const int tiles = tiles_of_len(kv.seq_lens[b]);
+  const int rq = request_of(kv, b);
+  const int tiles = tiles_of_len(kv.seq_lens[rq]);
   const int u0 = ws.ureq[b] + g * tiles;
   const int w0 = range_of(u0, total, ws.n_ranges), w1 = range_of(u0 + tiles - 1, total, ws.n_ranges);
   if (w1 == w0) return;
@@ -640,7 +649,7 @@ __global__ __launch_bounds__(256) void verify_o_merge_range(KvView kv, int n_q, 
       acc += *reinterpret_cast<const f32x4*>(ws.part_o + (static_cast<int64_t>(pair + w) * R + r) * kHeadDim + 4 * d4);
     }
     const int i = r / G, hg = r - i * G;
-    uint16_t* dst = out + ((static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg) * kHeadDim;
+    uint16_t* dst = out + ((static_cast<int64_t>(rq) * n_q + i) * kv.num_q_heads + g * G + hg) * kHeadDim;
     u32x2 pk;
     pk.x = pack2(acc.x, acc.y);
     pk.y = pack2(acc.z, acc.w);
@@ -681,13 +690,13 @@ __device__ __forceinline__ int stash_lane(int rb, int nblocks, int nv, int n, in
   return rb < nblocks - 1 ? rb * 64 + lane : (n < nv ? (nblocks - 1) * 64 + g4 * nv + n : -1);
 }
 
+// Range w of the single pass, by one wavefront (lane = its lane index) with its own LDS: a tile buffer of
+// kVTileBytes and (RB * 16 + 1) query rows of kKRow bytes.
 template <int RB, bool FP8, bool STASH>
-__global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, const uint16_t* q, int n_q, RangeWs ws, uint16_t* out) {
+__device__ __forceinline__ void flash_range_body(const KvView& kv, const uint16_t* q, int n_q, const RangeWs& ws, uint16_t* out,
+                                                 uint8_t* s_tile, uint8_t* s_q, int w, int lane) {
   static_assert(RB <= 2, "3 and 4 row blocks run verify_flash_pair");
   constexpr int DEPTH = 1;                     // tiles in flight (two wavefronts share a SIMD's registers: no room for more)
-  __shared__ __attribute__((aligned(16))) uint8_t s_tile[kVTileBytes];
-  __shared__ __attribute__((aligned(16))) uint8_t s_q[(RB * 16 + 1) * kKRow];
-  const int lane = threadIdx.x;
   const int n = lane & 15, g4 = lane >> 4;
   const int G = kv.num_q_heads / kv.num_kv_heads;
   const int R = n_q * G;
@@ -697,7 +706,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, con
   const LaneGeom<FP8> geo = lane_geom<FP8>(kv, lane);
   constexpr int kLoads = TileRegs<FP8>::kLoads;
   constexpr int kQIters = ((RB * 16 + 1) * 16 + kThreads - 1) / kThreads;
-  Cursor cur = open_cursor(kv, ws, lane);
+  Cursor cur = open_cursor(kv, ws, w, lane);
   if (!cur.live) return;
   int unit = cur.unit;                         // global index of the tile being computed
   u32x4 rk[DEPTH][kLoads], rv[DEPTH][kLoads];
@@ -724,7 +733,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, con
       if (whole) {
         const float inv = l > 0.f ? 1.0f / l : 0.f;       // a row that sees no token: zeros
         const int i = r / G, hg = r - i * G;
-        uint16_t* dst = out + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim;
+        uint16_t* dst = out + ((static_cast<int64_t>(cs.rq) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim;
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
           u32x2 pk;
@@ -744,7 +753,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, con
       if (started) finish();
       cs = f.sg;
       started = true;
-      nq_b = __builtin_amdgcn_readfirstlane(queries_of(ws, cs.b, n_q));
+      nq_b = __builtin_amdgcn_readfirstlane(queries_of(kv, ws, cs.b, n_q));
       Rb = nq_b * G;
       {                                        // Q rows of the pair -> LDS (row R is the zero row of the padding)
         u32x4 qtmp[kQIters];
@@ -755,7 +764,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, con
           u32x4 v = {0u, 0u, 0u, 0u};
           if (r < Rb) {
             const int i = r / G, hg = r - i * G;
-            v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim + 8 * c);
+            v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(cs.rq) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim + 8 * c);
           }
           qtmp[j] = v;
         }
@@ -849,6 +858,37 @@ __global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, con
     }
   }
   finish();
+}
+
+template <int RB, bool FP8, bool STASH>
+__global__ __launch_bounds__(kThreads, 2) void verify_flash_range(KvView kv, const uint16_t* q, int n_q, RangeWs ws, uint16_t* out) {
+  __shared__ __attribute__((aligned(16))) uint8_t s_tile[kVTileBytes];
+  __shared__ __attribute__((aligned(16))) uint8_t s_q[(RB * 16 + 1) * kKRow];
+  flash_range_body<RB, FP8, STASH>(kv, q, n_q, ws, out, s_tile, s_q, blockIdx.x, threadIdx.x);
+}
+
+// A unified batch in one grid (paper Section 4.2, "Fused Sparse and Full Attention"): the first n_groups
+// workgroups carry four ranges of the verification pass each (one per wavefront, as independent as in their own
+// kernel), the workgroups after them one (request, KV head, span) of the draft step each.  Which path a
+// workgroup takes is decided on the chip from its index; the draft workgroups come last in dispatch order, so
+// they fill the compute units as the ranges drain.
+template <int RB, bool FP8>
+__global__ __launch_bounds__(4 * kThreads, 2) void mixed_flash_span(KvView kv, const uint16_t* q, int n_q, RangeWs ws, uint16_t* out,
+                                                                    int n_groups, DecodeArgs da, DecWs dws, int span_rows, int nspan) {
+  constexpr int kFlashLds = kVTileBytes + (RB * 16 + 1) * kKRow;        // of one wavefront of the verification pass
+  static_assert(kFlashLds % 16 == 0 && kFlashLds >= kVTileBytes, "the draft path uses the same memory as four tile buffers");
+  __shared__ __attribute__((aligned(16))) uint8_t smem[4 * kFlashLds];
+  if (static_cast<int>(blockIdx.x) < n_groups) {
+    const int wave = threadIdx.x / kThreads, lane = threadIdx.x & (kThreads - 1);
+    const int w = blockIdx.x * 4 + wave;
+    if (w < ws.n_ranges)
+      flash_range_body<RB, FP8, true>(kv, q, n_q, ws, out, smem + wave * kFlashLds, smem + wave * kFlashLds + kVTileBytes, w, lane);
+  } else {
+    const int i = blockIdx.x - n_groups;
+    const int sp = i % nspan, pg = i / nspan;
+    decode_span_body<FP8>(da, dws, span_rows, nspan, pg / da.kv.num_kv_heads, pg % da.kv.num_kv_heads, sp,
+                          reinterpret_cast<uint8_t (*)[kVTileBytes]>(smem));
+  }
 }
 
 // ------------------------------------------ 3 and 4 row blocks: two wavefronts per range ----
@@ -969,7 +1009,7 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
   constexpr int kHalf = HalfRegs<FP8>::kLoads;
   constexpr int kRowsPerLoad = FP8 ? 8 : 4;
   constexpr int kQIters = ((RB * 16 + 1) * 16 + kPairThreads - 1) / kPairThreads;
-  Cursor cur = open_cursor(kv, ws, lane);
+  Cursor cur = open_cursor(kv, ws, blockIdx.x, lane);
   if (!cur.live) return;                       // the same for both wavefronts
   int unit = cur.unit;
   u32x4 rk[kHalf], rv[kHalf];
@@ -993,7 +1033,7 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
       if (whole) {
         const float inv = l > 0.f ? 1.0f / l : 0.f;       // a row that sees no token: zeros
         const int i = r / G, hg = r - i * G;
-        uint16_t* dst = out + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim;
+        uint16_t* dst = out + ((static_cast<int64_t>(cs.rq) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim;
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
           u32x2 pk;
@@ -1014,7 +1054,7 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
       if (started) finish();
       cs = f.sg;
       started = true;
-      nq_b = __builtin_amdgcn_readfirstlane(queries_of(ws, cs.b, n_q));
+      nq_b = __builtin_amdgcn_readfirstlane(queries_of(kv, ws, cs.b, n_q));
       Rb = nq_b * G;
       {                                        // Q rows of the pair -> LDS, by both wavefronts (row R is the zero row)
         u32x4 qtmp[kQIters];
@@ -1025,7 +1065,7 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
           u32x4 v = {0u, 0u, 0u, 0u};
           if (r < Rb) {
             const int i = r / G, hg = r - i * G;
-            v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(cs.b) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim + 8 * c);
+            v = *reinterpret_cast<const u32x4*>(q + ((static_cast<int64_t>(cs.rq) * n_q + i) * kv.num_q_heads + cs.g * G + hg) * kHeadDim + 8 * c);
           }
           qtmp[j] = v;
         }
@@ -1156,11 +1196,12 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
   __shared__ SelectLds<THREADS, CH> lds;
   const int pair = ws.order[blockIdx.x];
   const int b = pair / kv.num_kv_heads, g = pair - b * kv.num_kv_heads;
-  const int L = kv.seq_lens[b];
+  const int rq = request_of(kv, b);
+  const int L = kv.seq_lens[rq];
   const int tiles = tiles_of_len(L);
   const int G = kv.num_q_heads / kv.num_kv_heads;
   const int R = n_q * G;
-  const int Rb = queries_of(ws, b, n_q) * G;
+  const int Rb = queries_of(kv, ws, b, n_q) * G;
   constexpr int rows = RB * 16;
   const int total = ws.ctrl[0];
   const int u0 = ws.ureq[b] + g * tiles;
@@ -1168,9 +1209,9 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
   int K = 0;
   int32_t* out_idx = nullptr;
   if constexpr (SELECT) {
-    K = max(0, min(min(sel.budgets[b], L), sel.max_budget));
-    out_idx = sel.indices + static_cast<int64_t>(pair) * sel.max_budget;
-    if (g == 0 && threadIdx.x == 0) sel.counts[b] = K;
+    K = max(0, min(min(sel.budgets[rq], L), sel.max_budget));
+    out_idx = sel.indices + (static_cast<int64_t>(rq) * kv.num_kv_heads + g) * sel.max_budget;
+    if (g == 0 && threadIdx.x == 0) sel.counts[rq] = K;
     for (int j = K + threadIdx.x; j < sel.max_budget; j += THREADS) out_idx[j] = -1;
   }
 
@@ -1250,14 +1291,14 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
     s_lse[row] = v;
     if (lse_out && row < Rb) {
       const int i = row / G, hg = row - i * G;
-      lse_out[(static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg] = live ? v * kLn2 : -INFINITY;
+      lse_out[(static_cast<int64_t>(rq) * n_q + i) * kv.num_q_heads + g * G + hg] = live ? v * kLn2 : -INFINITY;
     }
   }
   __syncthreads();
   if (split) {
     auto store_o = [&](int r, int d4, const f32x4& acc) {
       const int i = r / G, hg = r - i * G;
-      uint16_t* dst = out + ((static_cast<int64_t>(b) * n_q + i) * kv.num_q_heads + g * G + hg) * kHeadDim;
+      uint16_t* dst = out + ((static_cast<int64_t>(rq) * n_q + i) * kv.num_q_heads + g * G + hg) * kHeadDim;
       u32x2 pk;
       pk.x = pack2(acc.x, acc.y);
       pk.y = pack2(acc.z, acc.w);
@@ -1316,7 +1357,7 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
       if (n == 0) *reinterpret_cast<f32x4*>(s_scores + slot * kTileTokens + 16 * sub + 4 * g4) = tot[sub];
     }
   };
-  float* sdst = scores ? scores + static_cast<int64_t>(pair) * score_stride : nullptr;
+  float* sdst = scores ? scores + (static_cast<int64_t>(rq) * kv.num_kv_heads + g) * score_stride : nullptr;
   uint32_t key[CH][KPC];
   auto chunk = [&](int c, uint32_t (&keys)[KPC]) {
     const int t_begin = c * kChunkTiles, t_end = min(tiles, t_begin + kChunkTiles);
@@ -1417,7 +1458,7 @@ RangeWs carve(const KvView& kv, int n_q, void* workspace, size_t* total_bytes) {
 }
 
 template <int RB, bool FP8>
-hipError_t run(const VerifyArgs& a, hipStream_t st) {
+hipError_t run(const VerifyArgs& a, hipStream_t st, const DecodeArgs* draft) {
   const KvView& kv = a.kv;
   RangeWs ws = carve(kv, a.n_q, a.workspace, nullptr);
   ws.spec_lens = a.spec_lens;
@@ -1429,7 +1470,21 @@ hipError_t run(const VerifyArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(range_plan, dim3(1), dim3(1024), 0, st, kv, ws);
   }
   if (!a.exact_scores || !(a.scores || a.select)) {
-    {
+    bool fused = false;
+    if constexpr (RB <= 2) {
+      if (draft) {                             // a unified batch: the draft step of other requests rides in the same grid
+        fused = true;
+        KernelTimer t("mixed_flash_span", st);
+        const int span_rows = decode_span_rows(draft->kv, draft->max_budget);
+        const int nspan = (draft->max_budget + span_rows - 1) / span_rows;
+        const DecWs dws = decode_carve(draft->kv, draft->max_budget, draft->workspace);
+        const int n_groups = (ws.n_ranges + 3) / 4;
+        const int n_draft = nspan * draft->kv.num_kv_heads * draft->kv.batch;
+        hipLaunchKernelGGL((mixed_flash_span<RB, FP8>), dim3(n_groups + n_draft), dim3(4 * kThreads), 0, st, kv, q, a.n_q, ws, out,
+                           n_groups, *draft, dws, span_rows, nspan);
+      }
+    }
+    if (!fused) {
       KernelTimer t("verify_flash_range", st);
       const bool stash = a.scores || a.select;
       if constexpr (RB >= 3) {                 // two wavefronts per range
@@ -1458,6 +1513,10 @@ hipError_t run(const VerifyArgs& a, hipStream_t st) {
       else if (kv.max_seq_len <= 16384) PILLAR_FINISH(1024, 2, true);
       else PILLAR_FINISH(1024, 4, true);
 #undef PILLAR_FINISH
+    }
+    if (fused) {
+      const hipError_t e = launch_decode_merge(*draft, st);      // only lists longer than one span leave partials
+      if (e != hipSuccess) return e;
     }
     return hipGetLastError();
   }
@@ -1514,11 +1573,16 @@ size_t verify_range_workspace(const KvView& kv, int n_q) {
   return total;
 }
 
-hipError_t launch_verify_range(const VerifyArgs& a, hipStream_t s) {
+bool verify_fuses_draft(const VerifyArgs& a) {
+  // the fused grid holds the single-wavefront pass (up to 32 query rows) with its statistic and in-kernel selection
+  return verify_select_fused(a) && row_blocks(a.kv, a.n_q) <= 2;
+}
+
+hipError_t launch_verify_range(const VerifyArgs& a, hipStream_t s, const DecodeArgs* fused_draft) {
   const int rb = row_blocks(a.kv, a.n_q);
   const bool fp8 = a.kv_dtype == PILLAR_FP8_E4M3;
 #define PILLAR_CASE(N) \
-  if (rb == N) return fp8 ? run<N, true>(a, s) : run<N, false>(a, s);
+  if (rb == N) return fp8 ? run<N, true>(a, s, fused_draft) : run<N, false>(a, s, fused_draft);
   PILLAR_CASE(1)
   PILLAR_CASE(2)
   PILLAR_CASE(3)

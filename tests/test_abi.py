@@ -132,6 +132,22 @@ def test_bad_call_arguments_are_rejected(lib):
     assert sd(cnt=None) == pb.PILLAR_EINVAL and sd(out=None) == pb.PILLAR_EINVAL and sd(mb=0) == pb.PILLAR_EINVAL
 
 
+def test_mixed_step_arguments(lib):
+    s = good_kv()
+    def ms(kv=s, vids=FAKE, nv=2, dids=FAKE, nd=2, qv=FAKE, outv=FAKE, budgets=FAKE, mb=256, idx=FAKE, cnt=FAKE, qd=FAKE, outd=FAKE,
+           ws=FAKE, wsz=1 << 40):
+        return lib.pillar_mixed_step(C.byref(kv), vids, nv, dids, nd, qv, 4, outv, None, None, 0, budgets, mb, idx, cnt, qd, outd, None,
+                                     ws, wsz, None)
+    assert ms(nv=-1) == pb.PILLAR_EINVAL and ms(nd=5) == pb.PILLAR_EINVAL          # more than the batch holds
+    assert ms(vids=None) == pb.PILLAR_EINVAL and ms(dids=None) == pb.PILLAR_EINVAL
+    assert ms(qv=None) == pb.PILLAR_EINVAL and ms(outd=None) == pb.PILLAR_EINVAL
+    assert ms(budgets=None) == pb.PILLAR_EINVAL and ms(mb=0) == pb.PILLAR_EINVAL and ms(cnt=None) == pb.PILLAR_EINVAL
+    assert ms(ws=None) == pb.PILLAR_EWORKSPACE and ms(wsz=128) == pb.PILLAR_EWORKSPACE
+    assert ms(kv=good_kv(flags=pb.PILLAR_FLAG_EXACT_SCORES)) == pb.PILLAR_EUNSUPPORTED
+    assert ms(kv=good_kv(q_dtype=pb.PILLAR_F32, kv_dtype=pb.PILLAR_F32)) == pb.PILLAR_EUNSUPPORTED
+    assert ms(nv=0, nd=0, vids=None, dids=None, qv=None, outv=None, qd=None, outd=None) == pb.PILLAR_OK     # nothing to do
+
+
 def test_static_decode_rejects_what_its_scratch_cannot_hold(lib):
     sds = lambda s, mb=256, q=FAKE: lib.pillar_sparse_decode_static(C.byref(s), q, FAKE, FAKE, mb, FAKE, None, None)
     assert sds(good_kv(), q=None) == pb.PILLAR_EINVAL and sds(good_kv(), mb=0) == pb.PILLAR_EINVAL
