@@ -85,9 +85,12 @@ __global__ __launch_bounds__(1024) void range_plan(KvView kv, RangeWs ws) {
   __shared__ int32_t carry;
   if (threadIdx.x == 0) carry = 0;
   __syncthreads();
+  int first_len = 0;                           // length of request threadIdx.x (first pass), for the ranking below
   for (int b0 = 0; b0 < kv.batch; b0 += 1024) {
     const int b = b0 + threadIdx.x;
-    const int mine = b < kv.batch ? tiles_of_len(kv.seq_lens[request_of(kv, b)]) * kv.num_kv_heads : 0;
+    const int len_b = b < kv.batch ? kv.seq_lens[request_of(kv, b)] : 0;
+    if (b0 == 0) first_len = len_b;
+    const int mine = b < kv.batch ? tiles_of_len(len_b) * kv.num_kv_heads : 0;
     scan[threadIdx.x] = mine;
     __syncthreads();
     for (int o = 1; o < 1024; o <<= 1) {
@@ -109,7 +112,7 @@ __global__ __launch_bounds__(1024) void range_plan(KvView kv, RangeWs ws) {
   if (kv.batch <= 1024) {
     __syncthreads();
     const int b = threadIdx.x;
-    const int len = b < kv.batch ? kv.seq_lens[request_of(kv, b)] : 0;
+    const int len = first_len;
     scan[threadIdx.x] = len;
     __syncthreads();
     if (b < kv.batch) {
@@ -1507,8 +1510,12 @@ hipError_t run(const VerifyArgs& a, hipStream_t st, const DecodeArgs* draft) {
 #define PILLAR_FINISH(THREADS, CH, SELECT)                                                                                    \
   hipLaunchKernelGGL((verify_finish<RB, THREADS, CH, SELECT>), dim3(pairs), dim3(THREADS), 0, st, kv, a.n_q, ws, out, a.lse, \
                      a.scores, a.score_stride, sel)
+      // few pairs (a unified batch with a handful of verifying requests): every pair gets 16 wavefronts, the
+      // kernel then lasts as long as its longest pair
+      const bool few = pairs <= 2 * num_cus();
       if (!a.select) PILLAR_FINISH(512, 1, false);
       else if (kv.max_seq_len <= 4096) PILLAR_FINISH(512, 1, true);
+      else if (kv.max_seq_len <= 8192 && few) PILLAR_FINISH(1024, 1, true);
       else if (kv.max_seq_len <= 8192) PILLAR_FINISH(512, 2, true);
       else if (kv.max_seq_len <= 16384) PILLAR_FINISH(1024, 2, true);
       else PILLAR_FINISH(1024, 4, true);
