@@ -31,6 +31,32 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v) {
   return static_cast<uint32_t>(x);
 }
 
+// minimum / maximum over the 64 lanes of a wavefront, uniform result: the same DPP ladder as the prefix sum (lanes
+// without a source keep the identity), the total ends up in the last lane
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+  int x = static_cast<int>(v);
+  const int id = -1;                               // 0xffffffff
+  auto mn = [](int a, int b) { return static_cast<int>(min(static_cast<uint32_t>(a), static_cast<uint32_t>(b))); };
+  x = mn(x, __builtin_amdgcn_update_dpp(id, x, 0x111, 0xF, 0xF, false));
+  x = mn(x, __builtin_amdgcn_update_dpp(id, x, 0x112, 0xF, 0xF, false));
+  x = mn(x, __builtin_amdgcn_update_dpp(id, x, 0x114, 0xF, 0xF, false));
+  x = mn(x, __builtin_amdgcn_update_dpp(id, x, 0x118, 0xF, 0xF, false));
+  x = mn(x, __builtin_amdgcn_update_dpp(id, x, 0x142, 0xA, 0xF, false));
+  x = mn(x, __builtin_amdgcn_update_dpp(id, x, 0x143, 0xC, 0xF, false));
+  return static_cast<uint32_t>(__builtin_amdgcn_readlane(x, kWave - 1));
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  int x = static_cast<int>(v);
+  auto mx = [](int a, int b) { return static_cast<int>(max(static_cast<uint32_t>(a), static_cast<uint32_t>(b))); };
+  x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, false));
+  x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, false));
+  x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, false));
+  x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, false));
+  x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false));
+  x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false));
+  return static_cast<uint32_t>(__builtin_amdgcn_readlane(x, kWave - 1));
+}
+
 // LDS the selection needs (one instance per workgroup of THREADS threads holding CH chunks of keys).
 template <int THREADS, int CH> struct SelectLds {
   uint32_t hist[4096];
@@ -67,21 +93,31 @@ __device__ __forceinline__ void select_topk_in_registers(const uint32_t (&key)[C
         for (int i = threadIdx.x; i < 4096; i += THREADS) hist[i] = 0;
         __syncthreads();
       }
+      // A wavefront whose active keys all fall into one bin (constant or zero scores, or the few keys left in a late
+      // pass) adds their number once instead of queueing up on one LDS address; otherwise every key adds itself.
+      uint32_t lo = 0xffffffffu, hi = 0u, mine = 0u;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
 #pragma unroll
         for (int j = 0; j < KPC; ++j) {
           const bool act = c * kChunk + t0 + j < L && (key[c][j] & mask) == prefix;
           const uint32_t bin = (key[c][j] >> shift) & digit_mask;
-          // a wavefront whose active lanes all hit one bin (constant or zero scores) adds once
-          const uint64_t m = __ballot(act);
-          if (m == 0) continue;
-          const int leader = __ffsll(static_cast<long long>(m)) - 1;
-          const uint32_t leader_bin = __shfl(bin, leader, kWave);
-          if (__all(!act || bin == leader_bin)) {
-            if (lane == leader) atomicAdd(&hist[leader_bin], static_cast<uint32_t>(__popcll(m)));
-          } else if (act) {
-            atomicAdd(&hist[bin], 1u);
+          lo = act ? min(lo, bin) : lo;
+          hi = act ? max(hi, bin) : hi;
+          mine += act ? 1u : 0u;
+        }
+      }
+      const uint32_t wave_lo = wave_min_u32(lo), wave_hi = wave_max_u32(hi);
+      if (wave_lo >= wave_hi) {                  // one bin, or no active key at all (lo = ~0 > hi = 0)
+        const uint32_t total = wave_inclusive_sum(mine);
+        if (lane == kWave - 1 && total > 0) atomicAdd(&hist[wave_lo], total);
+      } else {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+#pragma unroll
+          for (int j = 0; j < KPC; ++j) {
+            const bool act = c * kChunk + t0 + j < L && (key[c][j] & mask) == prefix;
+            if (act) atomicAdd(&hist[(key[c][j] >> shift) & digit_mask], 1u);
           }
         }
       }
