@@ -41,6 +41,8 @@ struct VerifyArgs {
   const SelectOut* select = nullptr;   // non-null: also select the Top-K of every (request, KV head)
   bool exact_scores = false;           // PILLAR_FLAG_EXACT_SCORES: K read twice, fp32 probabilities
   const int32_t* spec_lens = nullptr;  // non-null: device [B], request b speculates spec_lens[b] <= n_q - 1 tokens
+  float* scratch_scores = nullptr;     // with select: room for the statistic ([slots][Hkv][scratch_stride]) if scores is null
+  int64_t scratch_stride = 0;
 };
 
 struct DecodeArgs {

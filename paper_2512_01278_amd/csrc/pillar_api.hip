@@ -193,6 +193,10 @@ int verify_common(const pillar_kv_t* kv, const void* q, int32_t spec_len_k, cons
   rc = check_workspace(workspace, workspace_bytes, stage_ws + (select ? scratch_scores_bytes(a.kv) : 0));
   if (rc != PILLAR_OK) return rc;
   const hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (select) {                                  // long rows pass the statistic between workgroups through memory
+    a.scratch_scores = reinterpret_cast<float*>(static_cast<char*>(workspace) + align_up(stage_ws, 256));
+    a.scratch_stride = static_cast<int64_t>(scratch_score_stride(a.kv));
+  }
   if (select && !(!generic && verify_select_fused(a))) {
     // two steps: the statistic goes through memory (the caller's buffer, or scratch behind the stage workspace)
     if (req_ids) return PILLAR_EUNSUPPORTED;      // (the stand-alone Top-K kernel knows no request lists)

@@ -53,6 +53,8 @@ struct RangeWs {
   int32_t* ctrl;        // [0] total units T
   int32_t* ureq;        // [B+1] first unit of request b (its heads follow each other)
   int32_t* order;       // [pairs] (request, head) pairs in the order the finish kernel takes them: longest rows first
+  float* scratch_scores;  // [pairs][scratch_stride] statistic of the split finish kernel when the caller wants none
+  int64_t scratch_stride;
   float* part_m;        // [pairs + N][rows_pad]  log2 domain
   float* part_l;        // [pairs + N][rows_pad]
   float* part_o;        // [pairs + N][R][128]
@@ -1187,9 +1189,15 @@ __global__ __launch_bounds__(2 * kThreads, RB >= 3 ? 2 : 3) void verify_flash_pa
 //      memory between two launches (paper Section 4.1: identification from the verification's own
 //      intermediates).
 // Rows of up to CH * THREADS * 8 tokens; without SELECT any length (the chunk loop is then a run-time one).
-template <int RB, int THREADS, int CH, bool SELECT>
+// SPLIT (long rows): a pair is shared by up to CH workgroups, blockIdx.y = the chunk of THREADS * 8 tokens each
+// of them rebuilds; the statistic goes to memory (the caller's buffer, else scratch) and verify_select_rows, the
+// next launch, selects from it.  The first chunk's workgroup also does step 1's output and step 2.  (Handing the
+// chunks to the last workgroup to arrive inside one launch was measured: the device-wide release every workgroup
+// then needs writes back the whole L2 behind it, 3 to 5 times the cost of the extra launch.)
+template <int RB, int THREADS, int CH, bool SELECT, bool SPLIT>
 __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, RangeWs ws, uint16_t* out, float* lse_out,
                                                          float* scores, int64_t score_stride, SelectOut sel) {
+  static_assert(!SPLIT || !SELECT, "a split pair is selected by verify_select_rows");
   constexpr int KPC = 8;
   constexpr int kChunk = THREADS * KPC;                      // tokens whose scores LDS holds at a time
   constexpr int kChunkTiles = kChunk / kTileTokens;
@@ -1209,6 +1217,9 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
   const int total = ws.ctrl[0];
   const int u0 = ws.ureq[b] + g * tiles;
   const int w0 = range_of(u0, total, ws.n_ranges), w1 = range_of(u0 + tiles - 1, total, ws.n_ranges);
+  const int my_chunk = SPLIT ? static_cast<int>(blockIdx.y) : 0;
+  if (SPLIT && my_chunk * kChunk >= L) return;          // this pair has fewer chunks (uniform over the workgroup)
+  const bool lead = my_chunk == 0;                       // the workgroup that writes what exists once per pair
   int K = 0;
   int32_t* out_idx = nullptr;
   if constexpr (SELECT) {
@@ -1222,7 +1233,7 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
   const int n = lane & 15, g4 = lane >> 4;
   const int nv = R - 16 * (RB - 1);
   const int tile_lanes = (RB - 1) * 64 + 4 * nv;
-  const bool want_scores = SELECT || scores;
+  const bool want_scores = SELECT || SPLIT || scores;
 
   // The stash stream: wavefronts take the tiles of a chunk in turn, kBufs tiles in flight each.
   constexpr int kBufs = THREADS >= 1024 ? 2 : 4;       // (a 1024-thread workgroup has 128 registers per lane)
@@ -1247,7 +1258,7 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
     for (int i = 0; i < kBufs; ++i)
       if (t_begin + wave + i * kWaves < t_end) fetch(t_begin + wave + i * kWaves, i);
   };
-  if (want_scores) prime(0);                           // needs nothing of steps 1 and 2: in flight meanwhile
+  if (want_scores) prime(my_chunk);                    // needs nothing of steps 1 and 2: in flight meanwhile
 
   // 1. log-sum-exp per row (log2 domain).  Rows beyond the request's own, and rows that see no token at all,
   // get +inf: their probabilities vanish wherever the log-sum-exp is applied.
@@ -1256,7 +1267,7 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
   constexpr int kSegs = THREADS >= 1024 ? 2 : 4;
   constexpr int kOuts = (RB * 16 * (kHeadDim / 4) + THREADS - 1) / THREADS;
   const int nseg = w1 - w0 + 1;
-  const bool split = w1 > w0;
+  const bool split = w1 > w0 && lead;
   const bool early = split && nseg <= kSegs && total >= ws.n_ranges;     // (no empty ranges when there are as many units as ranges)
   f32x4 po[kOuts][kSegs];
   float pm[kOuts][kSegs];
@@ -1292,7 +1303,7 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
     const bool live = row < Rb && l > 0.f;
     const float v = live ? m + log2f(l) : INFINITY;
     s_lse[row] = v;
-    if (lse_out && row < Rb) {
+    if (lse_out && row < Rb && lead) {
       const int i = row / G, hg = row - i * G;
       lse_out[(static_cast<int64_t>(rq) * n_q + i) * kv.num_q_heads + g * G + hg] = live ? v * kLn2 : -INFINITY;
     }
@@ -1361,10 +1372,11 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
     }
   };
   float* sdst = scores ? scores + (static_cast<int64_t>(rq) * kv.num_kv_heads + g) * score_stride : nullptr;
+  if (SPLIT && !sdst) sdst = ws.scratch_scores + static_cast<int64_t>(pair) * ws.scratch_stride;
   uint32_t key[CH][KPC];
   auto chunk = [&](int c, uint32_t (&keys)[KPC]) {
     const int t_begin = c * kChunkTiles, t_end = min(tiles, t_begin + kChunkTiles);
-    if (c > 0) prime(c);
+    if (c != my_chunk) prime(c);
     for (int tile = t_begin + wave; tile < t_end;) {
 #pragma unroll
       for (int i = 0; i < kBufs; ++i) {
@@ -1395,7 +1407,9 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
     }
     __syncthreads();                                   // the next chunk overwrites the scores
   };
-  if constexpr (SELECT) {
+  if constexpr (SPLIT) {
+    chunk(my_chunk, key[0]);                           // the scores of this chunk go to memory
+  } else if constexpr (SELECT) {
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
       if (c * kChunk < L) {                            // uniform over the workgroup
@@ -1409,6 +1423,45 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
   } else {
     for (int c = 0; c * kChunk < L; ++c) chunk(c, key[0]);
   }
+}
+
+// Top-K of the statistic of long rows, from memory: one workgroup per (request, KV head), longest first; thread t
+// holds positions c * 8192 + 8 t .. + 7 of each chunk c (the same ownership as in verify_finish).
+template <int CH>
+__global__ __launch_bounds__(1024) void verify_select_rows(KvView kv, RangeWs ws, const float* scores, int64_t score_stride,
+                                                           SelectOut sel) {
+  constexpr int THREADS = 1024, KPC = 8, kChunk = THREADS * KPC;
+  __shared__ SelectLds<THREADS, CH> lds;
+  const int pair = ws.order[blockIdx.x];
+  const int b = pair / kv.num_kv_heads, g = pair - b * kv.num_kv_heads;
+  const int rq = request_of(kv, b);
+  const int L = kv.seq_lens[rq];
+  const int K = max(0, min(min(sel.budgets[rq], L), sel.max_budget));
+  int32_t* out_idx = sel.indices + (static_cast<int64_t>(rq) * kv.num_kv_heads + g) * sel.max_budget;
+  if (g == 0 && threadIdx.x == 0) sel.counts[rq] = K;
+  for (int j = K + threadIdx.x; j < sel.max_budget; j += THREADS) out_idx[j] = -1;
+  if (K == 0) return;
+  const float* src = scores ? scores + (static_cast<int64_t>(rq) * kv.num_kv_heads + g) * score_stride
+                            : ws.scratch_scores + static_cast<int64_t>(pair) * ws.scratch_stride;
+  uint32_t key[CH][KPC];
+#pragma unroll
+  for (int c = 0; c < CH; ++c) {
+    const int p0 = c * kChunk + static_cast<int>(threadIdx.x) * KPC;
+#pragma unroll
+    for (int j = 0; j < KPC; j += 4) {
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (p0 + j + 3 < L) {
+        v = *reinterpret_cast<const f32x4*>(src + p0 + j);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (p0 + j + i < L) v[i] = src[p0 + j + i];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) key[c][j + i] = order_key(v[i]);
+    }
+  }
+  select_topk_in_registers<THREADS, KPC, CH>(key, L, K, out_idx, lds);
 }
 
 // ---------------------------------------------------------------- host ------
@@ -1445,6 +1498,8 @@ RangeWs carve(const KvView& kv, int n_q, void* workspace, size_t* total_bytes) {
   w.ctrl = reinterpret_cast<int32_t*>(take(64 * 4));
   w.ureq = reinterpret_cast<int32_t*>(take((static_cast<size_t>(kv.batch) + 1) * 4));
   w.order = reinterpret_cast<int32_t*>(take(pairs * 4));
+  w.scratch_scores = nullptr;
+  w.scratch_stride = 0;
   w.part_m = reinterpret_cast<float*>(take(slots * rpad * 4));
   w.part_l = reinterpret_cast<float*>(take(slots * rpad * 4));
   w.part_o = reinterpret_cast<float*>(take(slots * R * kHeadDim * 4));
@@ -1465,6 +1520,8 @@ hipError_t run(const VerifyArgs& a, hipStream_t st, const DecodeArgs* draft) {
   const KvView& kv = a.kv;
   RangeWs ws = carve(kv, a.n_q, a.workspace, nullptr);
   ws.spec_lens = a.spec_lens;
+  ws.scratch_scores = a.scratch_scores;
+  ws.scratch_stride = a.scratch_stride;
   const uint16_t* q = static_cast<const uint16_t*>(a.q);
   uint16_t* out = static_cast<uint16_t*>(a.out);
   const int pairs = kv.batch * kv.num_kv_heads;
@@ -1502,24 +1559,44 @@ hipError_t run(const VerifyArgs& a, hipStream_t st, const DecodeArgs* draft) {
           hipLaunchKernelGGL((verify_flash_range<RB, FP8, false>), dim3(ws.n_ranges), dim3(kThreads), 0, st, kv, q, a.n_q, ws, out);
       }
     }
+    int split_select = 0;                      // chunks per row when the selection is a launch of its own
+    SelectOut sel{};
     {
       // one workgroup per pair: log-sum-exp, O of split pairs, scores, selection
       KernelTimer t("verify_finish", st);
-      SelectOut none{};
-      const SelectOut& sel = a.select ? *a.select : none;
-#define PILLAR_FINISH(THREADS, CH, SELECT)                                                                                    \
-  hipLaunchKernelGGL((verify_finish<RB, THREADS, CH, SELECT>), dim3(pairs), dim3(THREADS), 0, st, kv, a.n_q, ws, out, a.lse, \
+      sel = a.select ? *a.select : SelectOut{};
+#define PILLAR_FINISH(THREADS, CH, SELECT)                                                                                           \
+  hipLaunchKernelGGL((verify_finish<RB, THREADS, CH, SELECT, false>), dim3(pairs), dim3(THREADS), 0, st, kv, a.n_q, ws, out, a.lse, \
                      a.scores, a.score_stride, sel)
+#define PILLAR_FINISH_SPLIT(CH)                                                                                                   \
+  {                                                                                                                               \
+    const int nchunks = (kv.max_seq_len + 8191) / 8192;                                                                           \
+    hipLaunchKernelGGL((verify_finish<RB, 1024, 1, false, true>), dim3(pairs, nchunks), dim3(1024), 0, st, kv, a.n_q, ws, out,    \
+                       a.lse, a.scores, a.score_stride, sel);                                                                     \
+    split_select = CH;                                                                                                            \
+  }
       // few pairs (a unified batch with a handful of verifying requests): every pair gets 16 wavefronts, the
-      // kernel then lasts as long as its longest pair
+      // kernel then lasts as long as its longest pair; rows beyond 8192 tokens are shared by several workgroups
       const bool few = pairs <= 2 * num_cus();
-      if (!a.select) PILLAR_FINISH(512, 1, false);
+      if (!a.select && a.scores && kv.max_seq_len > 8192 && pairs <= num_cus()) PILLAR_FINISH_SPLIT(0)   // (statistic only)
+      else if (!a.select) PILLAR_FINISH(512, 1, false);
       else if (kv.max_seq_len <= 4096) PILLAR_FINISH(512, 1, true);
       else if (kv.max_seq_len <= 8192 && few) PILLAR_FINISH(1024, 1, true);
       else if (kv.max_seq_len <= 8192) PILLAR_FINISH(512, 2, true);
+      // long rows: with fewer pairs than compute units a pair is shared by several workgroups (measured at 128 pairs
+      // of 28 K tokens: 121 against 142 us); with more pairs one workgroup per pair keeps everything in one launch
+      // (512 pairs of up to 32 K tokens: 149 against 163 us)
+      else if (kv.max_seq_len <= 16384 && pairs <= num_cus()) PILLAR_FINISH_SPLIT(2)
       else if (kv.max_seq_len <= 16384) PILLAR_FINISH(1024, 2, true);
+      else if (pairs <= num_cus()) PILLAR_FINISH_SPLIT(4)
       else PILLAR_FINISH(1024, 4, true);
+#undef PILLAR_FINISH_SPLIT
 #undef PILLAR_FINISH
+    }
+    if (split_select) {
+      KernelTimer t("verify_select_rows", st);
+      if (split_select == 2) hipLaunchKernelGGL((verify_select_rows<2>), dim3(pairs), dim3(1024), 0, st, kv, ws, a.scores, a.score_stride, sel);
+      else hipLaunchKernelGGL((verify_select_rows<4>), dim3(pairs), dim3(1024), 0, st, kv, ws, a.scores, a.score_stride, sel);
     }
     if (fused) {
       const hipError_t e = launch_decode_merge(*draft, st);      // only lists longer than one span leave partials
