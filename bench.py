@@ -60,6 +60,32 @@ def cpu_baseline(w, target_s: float = 12.0) -> dict:
             "sample_seconds": round(wall, 3)}
 
 
+def measured_ceilings(pa, torch, dev) -> dict:
+    """HBM read rates of THIS box with a plain read kernel (pillar_bench_read): a sequential stream over 2 GiB and
+    the same bytes as 4 KiB chunks in random order (the access pattern of 16-token pages of one KV head)."""
+    nbytes = 2 << 30
+    buf = torch.ones(nbytes // 4, dtype=torch.int32, device=dev)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    n = nbytes // 4096
+    order = torch.randperm(n, device=dev, generator=torch.Generator(device=dev).manual_seed(1)).to(torch.int32)
+    res = {}
+    for name, o in (("stream_read", None), ("random_4KiB_chunks", order)):
+        best = 0.0
+        for blocks in (1024, 2048, 4096):
+            pa.pillar_bench_read(buf, n, 4096, o, blocks, sink)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                pa.pillar_bench_read(buf, n, 4096, o, blocks, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, 5 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        res[name + "_GBps"] = round(best, 1)
+    del buf, order
+    return res
+
+
 def recorded_traffic(config: int):
     """HBM bytes per step of the verification stage as rocprofv3's FETCH_SIZE / WRITE_SIZE counters gave
     them (scaled by a copy kernel of known size) for this workload: a recorded figure, read from the
@@ -234,6 +260,18 @@ def main() -> int:
     wall_ms = (time.perf_counter() - t0) * 1e3
     gpu_ms = ev0.elapsed_time(ev1)
 
+    # the same `steps` steps once more, each between its own event pair on the launch stream: median per step
+    pairs_ev = []
+    for _ in range(args.steps):
+        a_ev, b_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a_ev.record(stream)
+        step()
+        b_ev.record(stream)
+        pairs_ev.append((a_ev, b_ev))
+    torch.cuda.synchronize()
+    per_step_us = sorted(x.elapsed_time(y) * 1e3 for x, y in pairs_ev)
+    median_us = per_step_us[len(per_step_us) // 2]
+
     # the same `steps` steps again with a HIP event pair around every kernel (recorded by the
     # library on the launch stream): per-kernel durations; the events themselves stretch the step
     pa.pillar_profile_reset()
@@ -268,6 +306,8 @@ def main() -> int:
     step_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
     q_tokens = w.B * w.n_q + w.B          # query tokens served per step: k+1 verified + 1 drafted per request
 
+    ceil = measured_ceilings(pa, torch, run.dev)
+    stream_ceiling = ceil["stream_read_GBps"]
     dom = max(prof, key=lambda k: prof[k][1], default=None)
     dom_us = prof[dom][1] * 1e3 / max(prof[dom][0], 1) if dom else 0.0
     dom_bytes = vb if dom and dom.startswith("verify") else db if dom and dom.startswith("decode") else tb
@@ -293,16 +333,26 @@ def main() -> int:
                    "selected_rows": w.selected_rows(), "truncated": args.batch is not None},
         "tokens_per_s": round(q_tokens / (ms_per_step * 1e-3), 1),
         "gpu_ms_per_step": round(gpu_ms / args.steps, 5),
+        "median_us_per_step": round(median_us, 2),
         "ms_per_step_with_kernel_events": round(prof_wall_ms / args.steps, 5),
         "stage_us": {k: round(v, 2) for k, v in stage_us.items()},
         "stage_gbps": {"verify": round(verify_gbps, 1), "draft": round(draft_gbps, 1), "step": round(step_gbps, 1)},
         "stage_frac_of_peak": {"verify": round(verify_gbps / HBM_PEAK_GBPS, 4),
                                "draft": round(draft_gbps / HBM_PEAK_GBPS, 4),
                                "step": round(step_gbps / HBM_PEAK_GBPS, 4)},
+        "measured_ceilings": ceil,
+        "stage_frac_of_stream_ceiling": {"verify": round(verify_gbps / stream_ceiling, 4),
+                                         "draft": round(draft_gbps / stream_ceiling, 4),
+                                         "step": round(step_gbps / stream_ceiling, 4)},
+        "cache_state": "steps run back to back on the same pools and lists: a verification streams 4-10x the 256 MB "
+                       "Infinity Cache, so no KV byte of one verification survives to the next; the rows a draft step "
+                       "gathers (selected rows, 5-7 % of the KV) are still cached when the next verification reads them, "
+                       "as they are in serving, where the draft steps of a round precede its verification",
         "algorithmic_bytes": {"verify": vb, "topk": tb, "draft": db},
         "kernels": kern,
         "roofline": {"bound": "hbm", "achieved": round(verify_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(verify_gbps / HBM_PEAK_GBPS, 4),
+                     "frac_of_stream_ceiling": round(verify_gbps / stream_ceiling, 4),
                      "traffic": None if args.batch is not None else recorded_traffic(args.config),
                      "kernel": "verification stage = " + " + ".join(sorted(k for k in prof if k.startswith("verify"))),
                      "avg_us": round(stage_us["verify"], 2), "algorithmic_bytes": vb,
@@ -311,8 +361,8 @@ def main() -> int:
                                          "frac": round(dom_gbps / HBM_PEAK_GBPS, 4)},
                      "note": "algorithmic bytes of the verification stage (every KV row once + one fp32 score per "
                              "token and KV head + Q and O) over the SUM of the average durations of all its kernels "
-                             "(HIP events on the launch stream): the method needs the log-sum-exp pass as much as the "
-                             "score pass, so the stage, not its longest kernel, is priced against the roofline; "
+                             "(HIP events on the launch stream): the method needs the finish kernel (log-sum-exp, scores) as "
+                             "much as the streaming pass, so the stage, not its longest kernel, is priced against the roofline; "
                              "dominant_kernel prices the same bytes against the longest kernel alone; with "
                              "pillar_verify_select the stage's time also contains the Top-K selection (its finish "
                              "kernel selects from on-chip scores) while its bytes do not; traffic is not "

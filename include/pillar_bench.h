@@ -32,6 +32,14 @@ void pillar_profile_enable(int on);
 void pillar_profile_reset(void);
 int  pillar_profile_read(pillar_kernel_time* entries, int cap);
 
+/* What the machine at hand delivers from HBM, for pricing a kernel against a measured ceiling beside the published
+ * peak: one launch of a plain read kernel.  Every wavefront of `blocks` 256-thread workgroups reads whole chunks of
+ * `chunk_bytes` (a multiple of 16) of `buf` (device, 16-byte aligned, at least n_chunks * chunk_bytes bytes past the
+ * largest chunk index) with streaming 16-byte loads: chunk order[i] if `order` (device int32 [n_chunks]) is given,
+ * else chunk i.  `sink`: 16 bytes of device memory that are never written in practice.  The caller times it. */
+int pillar_bench_read(const void* buf, int64_t n_chunks, int32_t chunk_bytes, const int32_t* order, int32_t blocks,
+                      void* sink, void* hip_stream);
+
 /* Launch-shape knobs for sweeps (process-wide, not thread-safe against running
  * calls; none of them changes a result bit).  Known names: "verify_waves"
  * (wavefronts per compute unit that the verification pass is divided among,

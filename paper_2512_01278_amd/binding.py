@@ -26,7 +26,7 @@ DTYPE_CODE = {"f32": PILLAR_F32, "bf16": PILLAR_BF16, "fp8_e4m3": PILLAR_FP8_E4M
 EXPORTS = ("pillar_version", "pillar_status_string", "pillar_workspace_bytes", "pillar_verify_attn",
            "pillar_verify_select", "pillar_verify_hetero", "pillar_mixed_step", "pillar_select_topk", "pillar_sparse_decode", "pillar_sparse_decode_static", "pillar_window_indices",
            "pillar_extend_indices", "pillar_append_kv", "pillar_profile_enable", "pillar_profile_reset",
-           "pillar_profile_read", "pillar_set_option")
+           "pillar_profile_read", "pillar_set_option", "pillar_bench_read")
 
 
 class pillar_kv_t(C.Structure):
@@ -103,6 +103,8 @@ def load() -> C.CDLL:
     lib.pillar_extend_indices.restype = C.c_int
     lib.pillar_extend_indices.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                           C.c_void_p]
+    lib.pillar_bench_read.restype = C.c_int
+    lib.pillar_bench_read.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.pillar_set_option.restype = C.c_int
     lib.pillar_set_option.argtypes = [C.c_char_p, C.c_int64]
     lib.pillar_profile_enable.restype = None
@@ -281,6 +283,12 @@ def pillar_extend_indices(indices: torch.Tensor, counts: torch.Tensor, first_new
     rc = load().pillar_extend_indices(indices.data_ptr(), counts.data_ptr(), first_new.data_ptr(), n_new.data_ptr(),
                                       indices.shape[0], indices.shape[1], indices.shape[2], _stream(stream))
     _check(rc, "pillar_extend_indices")
+
+
+def pillar_bench_read(buf: torch.Tensor, n_chunks: int, chunk_bytes: int, order: Optional[torch.Tensor], blocks: int,
+                      sink: torch.Tensor, stream=None) -> None:
+    _check(load().pillar_bench_read(buf.data_ptr(), n_chunks, chunk_bytes, _ptr(order), blocks, sink.data_ptr(), _stream(stream)),
+           "pillar_bench_read")
 
 
 def pillar_set_option(name: str, value: int) -> None:

@@ -141,6 +141,7 @@ __device__ __forceinline__ void select_topk_in_registers(const uint32_t (&key)[C
       if (lane == kWave - 1) lds.wave_sum[pass & 1][0][wave] = incl;
       __syncthreads();
       uint32_t before = 0;
+#pragma unroll 1
       for (int w = 0; w < wave; ++w) before += lds.wave_sum[pass & 1][0][w];
       incl += before;
       uint32_t above = incl - tot;           // keys in strictly higher digits than this thread's
@@ -191,6 +192,7 @@ __device__ __forceinline__ void select_topk_in_registers(const uint32_t (&key)[C
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
     uint32_t b_gt = 0, b_eq = 0, t_gt = 0, t_eq = 0;
+#pragma unroll 1
     for (int w = 0; w < kWaves; ++w) {
       const uint32_t a = lds.wave_sum[0][c][w], e = lds.wave_sum[1][c][w];
       if (w < wave) { b_gt += a; b_eq += e; }
