@@ -884,7 +884,7 @@ __global__ __launch_bounds__(4 * kThreads, 2) void mixed_flash_span(KvView kv, c
   static_assert(kFlashLds % 16 == 0 && kFlashLds >= kVTileBytes, "the draft path uses the same memory as four tile buffers");
   __shared__ __attribute__((aligned(16))) uint8_t smem[4 * kFlashLds];
   if (static_cast<int>(blockIdx.x) < n_groups) {
-    const int wave = threadIdx.x / kThreads, lane = threadIdx.x & (kThreads - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kThreads), lane = threadIdx.x & (kThreads - 1);   // scalar: LDS bases stay out of the vector registers
     const int w = blockIdx.x * 4 + wave;
     if (w < ws.n_ranges)
       flash_range_body<RB, FP8, true>(kv, q, n_q, ws, out, smem + wave * kFlashLds, smem + wave * kFlashLds + kVTileBytes, w, lane);
