@@ -11,12 +11,16 @@
 //                     unnormalised (m, l, O) partial per segment); the
 //                     exponentials e = exp2(s - m_tile) are left behind as
 //                     16-bit values (verify_flash_range; verify_flash_pair
-//                     with two wavefronts per range for more than 32 rows)
-//   combine           per (request, KV head): final log-sum-exp per row
-//   finish            scores = mean over rows of e * exp2(m_tile - lse), read
-//                     back from the stash (verify_score_finalize), or the same
-//                     plus Top-K from on-chip scores (verify_select_finish)
-//   merge             O = sum over segments of exp2(m_seg - lse) O_seg
+//                     with two wavefronts per range for more than 32 rows;
+//                     mixed_flash_span with the draft step of other requests
+//                     in the same grid, paper Section 4.2)
+//   finish            per (request, KV head), one launch (verify_finish):
+//                     log-sum-exp per row from the segments, O of pairs cut
+//                     into several segments, scores = mean over rows of
+//                     e * exp2(m_tile - lse) read back from the stash, and
+//                     Top-K of those scores while they are still on the chip
+//                     (long rows with few pairs: several workgroups per pair,
+//                     then verify_select_rows)
 //
 // Variant with fp32 probabilities, K read twice (PILLAR_FLAG_EXACT_SCORES):
 //   pass 1 (K only)   running (max, sum) per row -> (m, l) per row and segment
@@ -36,6 +40,9 @@
 // boundaries; the stretch of one pair inside one range is a segment, and the
 // segment of pair p in range w owns partial-result slot p + w (distinct
 // segments have distinct sums because both indices grow along the layout).
+// The plan (unit prefix per request, order of the pairs for the finish kernel)
+// is a small kernel of its own (range_plan), or, for the single pass with up to
+// 1024 requests, worked out by the wavefronts of the pass themselves (wave_plan).
 #include "launch.hpp"
 #include "mfma_tile.hpp"
 #include "topk_core.hpp"
@@ -64,6 +71,7 @@ struct RangeWs {
   const int32_t* spec_lens;   // [B] speculative length of each request, or null: all use the call's k
   int32_t rows_pad;     // 16 * row blocks
   int32_t n_ranges;     // N
+  int32_t plan_in_wave; // ctrl / ureq / order are not there yet: the wavefronts of the single pass work them out (wave_plan)
 };
 
 __host__ __device__ inline int tiles_of_len(int len) { return (len + kTileTokens - 1) / kTileTokens; }
@@ -271,25 +279,119 @@ __device__ __forceinline__ Segment uniform(const Segment& s) {
   return u;
 }
 
+// The plan without a launch of its own, for batches of up to 64 * kPlanRegs requests: every wavefront of the
+// single pass reads all lengths (lane l, register j: request 64 j + l) and scans them into the unit prefix, which
+// costs one round trip to memory where reading a finished plan costs three dependent ones.
+constexpr int kPlanRegs = 16;
+struct WavePlan {
+  int len[kPlanRegs];
+  int first[kPlanRegs];   // units before the request
+  int total;
+};
+
+__device__ __forceinline__ WavePlan wave_plan(const KvView& kv, int lane) {
+  WavePlan p;
+#pragma unroll
+  for (int j = 0; j < kPlanRegs; ++j) {
+    p.len[j] = 0;
+    if (kWave * j < kv.batch) {                // wave-uniform
+      const int b = kWave * j + lane;
+      if (b < kv.batch) p.len[j] = kv.seq_lens[request_of(kv, b)];
+    }
+  }
+  int carry = 0;
+#pragma unroll
+  for (int j = 0; j < kPlanRegs; ++j) {
+    p.first[j] = carry;
+    if (kWave * j < kv.batch) {
+      const int mine = tiles_of_len(p.len[j]) * kv.num_kv_heads;         // 0 beyond the batch
+      const int incl = static_cast<int>(wave_inclusive_sum(static_cast<uint32_t>(mine)));
+      p.first[j] = carry + incl - mine;
+      carry += __builtin_amdgcn_readlane(incl, kWave - 1);
+    }
+  }
+  p.total = carry;
+  return p;
+}
+
+// value of register set v for request b (wave-uniform)
+__device__ __forceinline__ int plan_get(const int (&v)[kPlanRegs], int b) {
+  int r = 0;
+#pragma unroll
+  for (int j = 0; j < kPlanRegs; ++j)
+    if (j == (b >> 6)) r = __builtin_amdgcn_readlane(v[j], b & (kWave - 1));
+  return r;
+}
+
+// What range_plan leaves in memory for the kernels after the pass, written by the pass itself: wavefront w ranks
+// requests w, w + N, ... by length (the order of the finish kernel: longest first, ties by index), wavefront 0
+// also writes the prefix.
+__device__ __forceinline__ void publish_plan(const KvView& kv, const RangeWs& ws, const WavePlan& p, int w, int lane) {
+  for (int r = w; r < kv.batch; r += ws.n_ranges) {
+    const int len_r = plan_get(p.len, r);
+    int rank = 0;
+#pragma unroll
+    for (int j = 0; j < kPlanRegs; ++j) {
+      if (kWave * j < kv.batch) {
+        const int b = kWave * j + lane;
+        const bool ahead = b < kv.batch && (p.len[j] > len_r || (p.len[j] == len_r && b < r));
+        rank += __popcll(__ballot(ahead));
+      }
+    }
+    for (int g = lane; g < kv.num_kv_heads; g += kWave) ws.order[rank * kv.num_kv_heads + g] = r * kv.num_kv_heads + g;
+  }
+  if (w == 0) {
+#pragma unroll
+    for (int j = 0; j < kPlanRegs; ++j) {
+      const int b = kWave * j + lane;
+      if (b < kv.batch) ws.ureq[b] = p.first[j];
+    }
+    if (lane == 0) {
+      ws.ureq[kv.batch] = p.total;
+      ws.ctrl[0] = p.total;
+    }
+  }
+}
+
 __device__ __forceinline__ Cursor open_cursor(const KvView& kv, const RangeWs& ws, int w, int lane) {
   Cursor c;
-  const int total = ws.ctrl[0];
   c.w = w;
-  c.unit = range_begin(c.w, total, ws.n_ranges);
-  c.end = range_begin(c.w + 1, total, ws.n_ranges);
-  c.live = c.unit < c.end;
   c.sg = Segment{};
   c.tile = 0;
   c.pw = PageWin{};
   c.pg_next = 0;
   c.len_next = 0;
-  if (!c.live) return c;
   Segment sg;
-  sg.b = find_request(ws, kv.batch, c.unit, lane);
-  sg.rq = __builtin_amdgcn_readfirstlane(request_of(kv, sg.b));
-  sg.L = __builtin_amdgcn_readfirstlane(kv.seq_lens[sg.rq]);
+  int first_unit;                              // of the request the range begins in
+  if (ws.plan_in_wave) {                       // the same for the whole grid
+    const WavePlan p = wave_plan(kv, lane);
+    publish_plan(kv, ws, p, w, lane);
+    c.unit = range_begin(c.w, p.total, ws.n_ranges);
+    c.end = range_begin(c.w + 1, p.total, ws.n_ranges);
+    c.live = c.unit < c.end;
+    if (!c.live) return c;
+    int upto = 0;                              // requests that begin at or before the unit
+#pragma unroll
+    for (int j = 0; j < kPlanRegs; ++j) {
+      if (kWave * j < kv.batch) upto += __popcll(__ballot(kWave * j + lane < kv.batch && p.first[j] <= c.unit));
+    }
+    sg.b = upto - 1;
+    sg.rq = __builtin_amdgcn_readfirstlane(request_of(kv, sg.b));
+    sg.L = plan_get(p.len, sg.b);
+    first_unit = plan_get(p.first, sg.b);
+  } else {
+    const int total = ws.ctrl[0];
+    c.unit = range_begin(c.w, total, ws.n_ranges);
+    c.end = range_begin(c.w + 1, total, ws.n_ranges);
+    c.live = c.unit < c.end;
+    if (!c.live) return c;
+    sg.b = find_request(ws, kv.batch, c.unit, lane);
+    sg.rq = __builtin_amdgcn_readfirstlane(request_of(kv, sg.b));
+    sg.L = __builtin_amdgcn_readfirstlane(kv.seq_lens[sg.rq]);
+    first_unit = __builtin_amdgcn_readfirstlane(ws.ureq[sg.b]);
+  }
   sg.tiles = tiles_of_len(sg.L);
-  const int rel = c.unit - __builtin_amdgcn_readfirstlane(ws.ureq[sg.b]);
+  const int rel = c.unit - first_unit;
   sg.g = rel / sg.tiles;
   sg.tile0 = rel - sg.g * sg.tiles;
   sg.tile1 = min(sg.tiles, sg.tile0 + (c.end - c.unit));
@@ -1524,6 +1626,7 @@ RangeWs carve(const KvView& kv, int n_q, void* workspace, size_t* total_bytes) {
   w.spec_lens = nullptr;
   w.rows_pad = static_cast<int32_t>(rpad);
   w.n_ranges = static_cast<int32_t>(n);
+  w.plan_in_wave = 0;
   if (total_bytes) *total_bytes = off;
   return w;
 }
@@ -1538,11 +1641,13 @@ hipError_t run(const VerifyArgs& a, hipStream_t st, const DecodeArgs* draft) {
   const uint16_t* q = static_cast<const uint16_t*>(a.q);
   uint16_t* out = static_cast<uint16_t*>(a.out);
   const int pairs = kv.batch * kv.num_kv_heads;
-  {
+  const bool single_pass = !a.exact_scores || !(a.scores || a.select);
+  ws.plan_in_wave = single_pass && kv.batch <= kWave * kPlanRegs;
+  if (!ws.plan_in_wave) {
     KernelTimer t("verify_range_plan", st);
     hipLaunchKernelGGL(range_plan, dim3(1), dim3(1024), 0, st, kv, ws);
   }
-  if (!a.exact_scores || !(a.scores || a.select)) {
+  if (single_pass) {
     bool fused = false;
     if constexpr (RB <= 2) {
       if (draft) {                             // a unified batch: the draft step of other requests rides in the same grid
@@ -1593,7 +1698,7 @@ hipError_t run(const VerifyArgs& a, hipStream_t st, const DecodeArgs* draft) {
       const bool few = pairs <= 2 * num_cus();
       if (!a.select && a.scores && kv.max_seq_len > 8192 && pairs <= num_cus()) PILLAR_FINISH_SPLIT(0)   // (statistic only)
       else if (!a.select) PILLAR_FINISH(512, 1, false);
-      else if (kv.max_seq_len <= 4096) PILLAR_FINISH(512, 1, true);
+      else if (kv.max_seq_len <= 4096 && !few) PILLAR_FINISH(512, 1, true);
       else if (kv.max_seq_len <= 8192 && few) PILLAR_FINISH(1024, 1, true);
       else if (kv.max_seq_len <= 8192) PILLAR_FINISH(512, 2, true);
       // long rows: with fewer pairs than compute units a pair is shared by several workgroups (measured at 128 pairs
