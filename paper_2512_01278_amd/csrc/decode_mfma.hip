@@ -33,7 +33,7 @@ constexpr int kSpanRows = 512;                 // rows of an index list one work
 template <bool FP8>
 __global__ __launch_bounds__(kDecThreads, 3) void decode_span_mfma(DecodeArgs a, DecWs ws, int span_rows, int nspan_max) {
   __shared__ __attribute__((aligned(16))) uint8_t s_tiles[kDecWaves][kVTileBytes];
-  decode_span_body<FP8>(a, ws, span_rows, nspan_max, blockIdx.z, blockIdx.y, blockIdx.x, s_tiles);
+  decode_span_body<FP8, kDecWaves>(a, ws, span_rows, nspan_max, blockIdx.z, blockIdx.y, blockIdx.x, s_tiles);
 }
 
 __global__ __launch_bounds__(kMergeThreads) void decode_merge_mfma(DecodeArgs a, DecWs ws, int split_rows, int nsplit_max) {

@@ -8,7 +8,7 @@
 namespace pillar {
 namespace {
 
-constexpr int kDecWaves = 4;                      // wavefronts per workgroup of the draft step
+constexpr int kDecWaves = 4;                      // wavefronts per workgroup of the draft kernel
 constexpr int kDecThreads = kDecWaves * kWave;
 
 // Resolved rows of two tiles: lane j < 32 holds row j of one tile, lane 32 + j row j of another.
@@ -55,10 +55,10 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return f32_to_bf16(a) | (static_cast<uint32_t>(f32_to_bf16(b)) << 16);
 }
 
-// One (request slot, KV head, span) of the draft step by a workgroup of kDecWaves wavefronts.  s_tiles: per
+// One (request slot, KV head, span) of the draft step by a workgroup of WAVES wavefronts.  s_tiles: per
 // wavefront one tile buffer (the K rows, then, once S^T is done, the V rows of the same tile; at the end its
 // (max, sum, O) for the combine).  Every thread of the workgroup must call this.
-template <bool FP8>
+template <bool FP8, int WAVES>
 __device__ __forceinline__ void decode_span_body(const DecodeArgs& a, const DecWs& ws, int span_rows, int nspan_max, int slot_b, int g,
                                                  int sp, uint8_t (*s_tiles)[kVTileBytes]) {
   const KvView& kv = a.kv;
@@ -69,11 +69,11 @@ __device__ __forceinline__ void decode_span_body(const DecodeArgs& a, const DecW
   uint8_t* s_tile = s_tiles[wave];
   const int32_t* list = a.indices + (static_cast<int64_t>(b) * kv.num_kv_heads + g) * a.max_budget;
   const int j_begin = sp * span_rows;
-  // The index entries of the first four tiles of this wavefront (tiles wave, wave + kDecWaves, ...; register q holds
+  // The index entries of the first four tiles of this wavefront (tiles wave, wave + WAVES, ...; register q holds
   // tile 2q in lanes 0..31 and tile 2q + 1 in lanes 32..63) leave together with the count: entries up to
   // max_budget exist, which of them count is decided when both are here.
   auto entry_of = [&](int round, int q) {
-    const int tile = wave + kDecWaves * (4 * round + 2 * q + (lane >> 5));
+    const int tile = wave + WAVES * (4 * round + 2 * q + (lane >> 5));
     return j_begin + tile * kTileTokens + (lane & 31);
   };
   int tok[2];
@@ -83,7 +83,7 @@ __device__ __forceinline__ void decode_span_body(const DecodeArgs& a, const DecW
   uint16_t* out = static_cast<uint16_t*>(a.out);
   if (count == 0) {
     if (sp == 0) {
-      for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kDecThreads)
+      for (int idx = threadIdx.x; idx < G * kHeadDim; idx += (WAVES * kWave))
         out[(static_cast<int64_t>(b) * kv.num_q_heads + g * G) * kHeadDim + idx] = 0;
       if (a.lse && threadIdx.x < G) a.lse[static_cast<int64_t>(b) * kv.num_q_heads + g * G + threadIdx.x] = -INFINITY;
     }
@@ -111,7 +111,7 @@ __device__ __forceinline__ void decode_span_body(const DecodeArgs& a, const DecW
     }
     TileRegs<FP8> regs;
     bool first = true;
-    for (int round = 0; wave + kDecWaves * 4 * round < ntiles; ++round) {
+    for (int round = 0; wave + WAVES * 4 * round < ntiles; ++round) {
       if (round > 0) {
 #pragma unroll
         for (int q = 0; q < 2; ++q) tok[q] = list[min(entry_of(round, q), a.max_budget - 1)];
@@ -126,15 +126,15 @@ __device__ __forceinline__ void decode_span_body(const DecodeArgs& a, const DecW
         const bool tile_there = e - (lane & 31) < j_end;
         rr[q] = resolve_rows<FP8>(kv, b, g, e < j_end ? tok[q] : tile_there ? head : 0);
       }
-      const int t_first = wave + kDecWaves * 4 * round;
+      const int t_first = wave + WAVES * 4 * round;
       issue_rows<FP8>(kv, rr[0], 0, regs, lane);
       for (int k = 0; k < 4; ++k) {
-        const int ti = t_first + kDecWaves * k;
+        const int ti = t_first + WAVES * k;
         if (ti >= ntiles) break;
         const int jb = j_begin + ti * kTileTokens;
         const Rows& cur = (k & 2) ? rr[1] : rr[0];
         const int half = k & 1;
-        const bool more = k < 3 && ti + kDecWaves < ntiles;
+        const bool more = k < 3 && ti + WAVES < ntiles;
         rows_to_lds<FP8, false>(regs.k, s_tile, lane);
         f32x4 s[2][1];
         tile_qk<1>(s_tile, qf, s, lane);
@@ -195,15 +195,15 @@ __device__ __forceinline__ void decode_span_body(const DecodeArgs& a, const DecW
     if (g4 == 0) { part[16 * kHeadDim + n] = m_run; part[16 * kHeadDim + 16 + n] = l_run; }
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * (kHeadDim / 4); idx += kDecThreads) {
+  for (int idx = threadIdx.x; idx < G * (kHeadDim / 4); idx += (WAVES * kWave)) {
     const int r = idx / (kHeadDim / 4), d4 = idx - r * (kHeadDim / 4);
     float m = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < kDecWaves; ++w) m = fmaxf(m, reinterpret_cast<const float*>(s_tiles[w])[16 * kHeadDim + r]);
+    for (int w = 0; w < WAVES; ++w) m = fmaxf(m, reinterpret_cast<const float*>(s_tiles[w])[16 * kHeadDim + r]);
     float l = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int w = 0; w < kDecWaves; ++w) {
+    for (int w = 0; w < WAVES; ++w) {
       const float* pw = reinterpret_cast<const float*>(s_tiles[w]);
       const float wgt = exp2f(pw[16 * kHeadDim + r] - m);        // m is finite: the first wavefront always has a tile
       l = fmaf(pw[16 * kHeadDim + 16 + r], wgt, l);

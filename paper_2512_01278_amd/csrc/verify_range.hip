@@ -993,7 +993,7 @@ __global__ __launch_bounds__(4 * kThreads, 2) void mixed_flash_span(KvView kv, c
   } else {
     const int i = blockIdx.x - n_groups;
     const int sp = i % nspan, pg = i / nspan;
-    decode_span_body<FP8>(da, dws, span_rows, nspan, pg / da.kv.num_kv_heads, pg % da.kv.num_kv_heads, sp,
+    decode_span_body<FP8, 4>(da, dws, span_rows, nspan, pg / da.kv.num_kv_heads, pg % da.kv.num_kv_heads, sp,
                           reinterpret_cast<uint8_t (*)[kVTileBytes]>(smem));
   }
 }
