@@ -74,6 +74,21 @@ def test_batch_larger_than_one_planning_pass():
     round_trip(w, what="1100 tiny requests")
 
 
+@pytest.mark.parametrize("waves", [0, 1])
+def test_plan_inside_the_pass_with_a_full_register_set(waves):
+    """1000 requests, many of equal length: the single pass works out its own plan (lengths of all requests in
+    16 registers per lane, ranks with ties by index); with one wavefront per compute unit there are fewer
+    wavefronts than requests, so each ranks several."""
+    rng = np.random.default_rng(19)
+    lens = rng.integers(3, 12, size=1000).tolist()
+    w = small(116, B=1000, Hq=4, Hkv=2, spec_k=2, seq_lens=lens, budgets=[4] * 1000)
+    pa.pillar_set_option("verify_waves", waves)
+    try:
+        round_trip(w, what=f"1000 tiny requests, verify_waves={waves}")
+    finally:
+        pa.pillar_set_option("verify_waves", 0)
+
+
 def test_few_wide_ranges_cross_pairs_and_page_windows():
     """One wavefront per compute unit: every range then covers several (request, head) pairs and
     more than the 64 pages a lane register holds, so segments, partial slots and page windows change
