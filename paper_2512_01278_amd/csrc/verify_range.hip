@@ -1596,11 +1596,18 @@ int num_cus() {
   return cus;
 }
 
-// wavefronts of pass 2 a compute unit holds at once (registers: 2 per SIMD up to 32 rows, else 1; LDS allows as many)
-int ranges_for(int rb) {
-  const int per_cu = rb >= 3 ? 4 : 8;
+// Ranges per compute unit: as many wavefronts as it holds at once (registers: 2 per SIMD up to 32 rows, else 1;
+// LDS allows as many).  Small workloads take fewer, down to half: below about 24 tiles per range the pass gains
+// nothing from more wavefronts, and every further cut of a pair is one more segment for the finish kernel to
+// merge (32 requests of 4096 tokens: finish 27 us with 8 per compute unit, 23 with 5, pass unchanged).
+int ranges_for(const KvView& kv, int rb) {
+  int per_cu = rb >= 3 ? 4 : 8;
   const int opt = options().verify_waves;
-  return (opt > 0 && opt <= per_cu ? opt : per_cu) * num_cus();
+  if (opt > 0 && opt <= per_cu) return opt * num_cus();
+  const int64_t units_max = static_cast<int64_t>(kv.batch) * kv.num_kv_heads * tiles_of_len(kv.max_seq_len);
+  const int fit = static_cast<int>(std::min<int64_t>(per_cu, units_max / (24 * static_cast<int64_t>(num_cus()))));
+  per_cu = std::max(per_cu / 2, fit);
+  return per_cu * num_cus();
 }
 
 int row_blocks(const KvView& kv, int n_q) { return (n_q * (kv.num_q_heads / kv.num_kv_heads) + 15) / 16; }
@@ -1610,7 +1617,7 @@ RangeWs carve(const KvView& kv, int n_q, void* workspace, size_t* total_bytes) {
   const size_t R = static_cast<size_t>(n_q) * G;
   const size_t rpad = (R + 15) / 16 * 16;
   const size_t pairs = static_cast<size_t>(kv.batch) * kv.num_kv_heads;
-  const size_t n = static_cast<size_t>(ranges_for(static_cast<int>(rpad / 16)));
+  const size_t n = static_cast<size_t>(ranges_for(kv, static_cast<int>(rpad / 16)));
   const size_t slots = pairs + n;
   char* p = static_cast<char*>(workspace);
   size_t off = 0;
