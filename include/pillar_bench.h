@@ -41,7 +41,7 @@ int pillar_bench_read(const void* buf, int64_t n_chunks, int32_t chunk_bytes, co
                       void* sink, void* hip_stream);
 
 /* Launch-shape knobs for sweeps (process-wide, not thread-safe against running
- * calls; none of them changes a result bit).  Known names: "verify_waves"
+ * calls; they change how the work is divided, and with it the order of floating-point sums, never what is computed).  Known names: "verify_waves"
  * (wavefronts per compute unit that the verification pass is divided among,
  * 1..8) and "decode_rows" (rows of the index list per workgroup of the draft
  * kernel, a multiple of 32 up to 4096; default 512).  A value of 0 restores the default.  Returns
