@@ -205,11 +205,11 @@ int pillar_sparse_decode(const pillar_kv_t* kv, const void* q, const int32_t* in
  *               written: a verifying request gets new out / lse / scores rows
  *               and a new index list and count; a drafting request reads its
  *               current list and gets out_draft / lse_draft rows.
- * Where the shapes allow it (up to 32 query rows per KV head) both phases run
- * in ONE grid: the workgroups of the streaming verification pass and those of
- * the draft step are dispatched to their code path on the chip; otherwise the
- * draft kernel is launched right after the verification's.  Either list may
- * be empty.  Matrix-core shapes only (bf16 queries, bf16 or fp8 KV, head_dim
+ * Both phases run in ONE grid: the workgroups of the streaming verification
+ * pass and those of the draft step are dispatched to their code path on the
+ * chip.  (A draft sum may be grouped differently than by pillar_sparse_decode:
+ * the results agree to rounding, not necessarily bit for bit, when a KV head
+ * has more than 32 query rows.)  Either list may be empty.  Matrix-core shapes only (bf16 queries, bf16 or fp8 KV, head_dim
  * 128, pages of >= 16 tokens, rows of up to 32768 tokens, flags 0); anything
  * else returns PILLAR_EUNSUPPORTED.  Workspace: pillar_workspace_bytes(). */
 int pillar_mixed_step(const pillar_kv_t* kv, const int32_t* verify_ids, int32_t n_verify,

@@ -1290,6 +1290,27 @@ __global__ __launch_bounds__(2 * kThreads, RB >= 3 ? 2 : 3) void verify_flash_pa
   else flash_pair_wave<RB, FP8, STASH, RB - kFirst, kFirst>(kv, q, n_q, ws, out, s_tile, s_q, 1);
 }
 
+// A unified batch with more than 32 query rows per KV head: the first n_ranges workgroups are those of
+// verify_flash_pair, the others carry one (request, KV head, span) of the draft step each, with two wavefronts.
+template <int RB, bool FP8>
+__global__ __launch_bounds__(2 * kThreads, 2) void mixed_flash_pair(KvView kv, const uint16_t* q, int n_q, RangeWs ws, uint16_t* out,
+                                                                    DecodeArgs da, DecWs dws, int span_rows, int nspan) {
+  static_assert(RB >= 3, "up to two row blocks run mixed_flash_span");
+  constexpr int kFirst = (RB + 1) / 2;
+  constexpr int kPassLds = kVTileBytes + (RB * 16 + 1) * kKRow;
+  static_assert(kPassLds >= 2 * kVTileBytes, "the draft path uses the same memory as two tile buffers");
+  __shared__ __attribute__((aligned(16))) uint8_t smem[kPassLds];
+  if (static_cast<int>(blockIdx.x) < ws.n_ranges) {
+    if (threadIdx.x < kThreads) flash_pair_wave<RB, FP8, true, kFirst, 0>(kv, q, n_q, ws, out, smem, smem + kVTileBytes, 0);
+    else flash_pair_wave<RB, FP8, true, RB - kFirst, kFirst>(kv, q, n_q, ws, out, smem, smem + kVTileBytes, 1);
+  } else {
+    const int i = blockIdx.x - ws.n_ranges;
+    const int sp = i % nspan, pg = i / nspan;
+    decode_span_body<FP8, 2>(da, dws, span_rows, nspan, pg / da.kv.num_kv_heads, pg % da.kv.num_kv_heads, sp,
+                             reinterpret_cast<uint8_t (*)[kVTileBytes]>(smem));
+  }
+}
+
 // Sort key of a score of the statistic: a mean of probabilities lies in [0, 1] (below 2 with any rounding), so the
 // sign bit and the top exponent bit of its pattern are zero and can go: the first 12-bit digit of the selection
 // then holds 6 exponent and 6 mantissa bits, 64 histogram bins per binade instead of 8, and scores that share a
@@ -1674,6 +1695,17 @@ hipError_t run(const VerifyArgs& a, hipStream_t st, const DecodeArgs* draft) {
         hipLaunchKernelGGL((mixed_flash_span<RB, FP8>), dim3(n_groups + n_draft), dim3(4 * kThreads), 0, st, kv, q, a.n_q, ws, out,
                            n_groups, *draft, dws, span_rows, nspan);
       }
+    } else {
+      if (draft) {                             // the same with two wavefronts per range and per draft workgroup
+        fused = true;
+        KernelTimer t("mixed_flash_pair", st);
+        const int span_rows = decode_span_rows(draft->kv, draft->max_budget);
+        const int nspan = (draft->max_budget + span_rows - 1) / span_rows;
+        const DecWs dws = decode_carve(draft->kv, draft->max_budget, draft->workspace);
+        const int n_draft = nspan * draft->kv.num_kv_heads * draft->kv.batch;
+        hipLaunchKernelGGL((mixed_flash_pair<RB, FP8>), dim3(ws.n_ranges + n_draft), dim3(2 * kThreads), 0, st, kv, q, a.n_q, ws, out,
+                           *draft, dws, span_rows, nspan);
+      }
     }
     if (!fused) {
       KernelTimer t("verify_flash_range", st);
@@ -1789,8 +1821,8 @@ size_t verify_range_workspace(const KvView& kv, int n_q) {
 }
 
 bool verify_fuses_draft(const VerifyArgs& a) {
-  // the fused grid holds the single-wavefront pass (up to 32 query rows) with its statistic and in-kernel selection
-  return verify_select_fused(a) && row_blocks(a.kv, a.n_q) <= 2;
+  // the fused grid holds the single pass with its statistic and in-kernel selection
+  return verify_select_fused(a);
 }
 
 hipError_t launch_verify_range(const VerifyArgs& a, hipStream_t s, const DecodeArgs* fused_draft) {

@@ -56,7 +56,7 @@ def _check_against_oracle(w, run, ver, dra, old_idx, old_cnt, what):
             assert np.isnan(d_out[b]).all() and np.isnan(d_lse[b]).all(), f"{what}: request {b} was drafted"
 
 
-def _case(w, ver, dra, what):
+def _case(w, ver, dra, what, draft_bits=True):
     print(f"[case] {what}: B={w.B} L={w.seq_lens.tolist()[:8]} verify={ver} draft={dra}", flush=True)
     run, old_idx, old_cnt = _prepare(w)
     _mixed(run, ver, dra)
@@ -69,6 +69,12 @@ def _case(w, ver, dra, what):
     torch.cuda.synchronize()
     for name in ("out", "lse", "scores", "indices", "counts", "d_out", "d_lse"):
         a, b = getattr(run, name), getattr(two, name)
+        if name.startswith("d_") and not draft_bits:
+            # more than 32 query rows: the draft workgroups of the fused grid have two wavefronts, those of the draft
+            # kernel four, so the partial sums of a list are grouped differently (both were compared with the oracle)
+            live = torch.as_tensor(sorted(dra), device=a.device, dtype=torch.long)
+            assert torch.allclose(a[live].float(), b[live].float(), rtol=2e-2, atol=2e-2), f"{what}: {name} differs from the two calls"
+            continue
         assert torch.equal(a.view(torch.uint8).flatten(), b.view(torch.uint8).flatten()), f"{what}: {name} differs from the two calls"
     print(f"[ok] {what}", flush=True)
 
@@ -87,10 +93,10 @@ def test_mixed_batch_long_lists_and_wide_groups():
     w = gen.make_custom(name="mixed-long", seed=402, B=4, Hq=16, Hkv=4, D=128, P=16, spec_k=2, q_dtype="bf16", kv_dtype="bf16",
                         seq_lens=[3000, 700, 2049, 1500], budgets=[1500, 300, 900, 100], sink_tokens=4)
     _case(w, [2], [0, 1, 3], "mixed batch, split lists")
-    # 40 query rows per KV head (fp8 KV): the verification runs two wavefronts per range, the draft follows it
+    # 40 query rows per KV head (fp8 KV): the verification runs two wavefronts per range, and so do the draft workgroups of the same grid
     w8 = gen.make_custom(name="mixed-fp8", seed=403, B=4, Hq=16, Hkv=2, D=128, P=16, spec_k=4, q_dtype="bf16",
                          kv_dtype="fp8_e4m3", seq_lens=[255, 1000, 40, 600], budgets=[16, 128, 8, 64])
-    _case(w8, [1, 2], [0, 3], "mixed batch, fp8, 40 rows")
+    _case(w8, [1, 2], [0, 3], "mixed batch, fp8, 40 rows", draft_bits=False)
 
 
 def test_mixed_batch_config3_reduced():
