@@ -336,6 +336,10 @@ def main() -> int:
         "median_us_per_step": round(median_us, 2),
         "ms_per_step_with_kernel_events": round(prof_wall_ms / args.steps, 5),
         "stage_us": {k: round(v, 2) for k, v in stage_us.items()},
+        # a round of the method = one verification (with selection) and spec_len_k draft steps on its lists
+        "round_us": round(stage_us["verify"] + stage_us["topk"] + w.spec_k * stage_us["draft"], 2),
+        "query_tokens_per_s": {"verify": round(w.B * (w.spec_k + 1) / max((stage_us["verify"] + stage_us["topk"]) * 1e-6, 1e-12), 1),
+                               "draft": round(w.B / max(stage_us["draft"] * 1e-6, 1e-12), 1)},
         "stage_gbps": {"verify": round(verify_gbps, 1), "draft": round(draft_gbps, 1), "step": round(step_gbps, 1)},
         "stage_frac_of_peak": {"verify": round(verify_gbps / HBM_PEAK_GBPS, 4),
                                "draft": round(draft_gbps / HBM_PEAK_GBPS, 4),
