@@ -236,6 +236,7 @@ struct Flight {
   Segment sg;
   int tb;            // first token of the tile
   int pages[2];      // pages of its two 16-token halves
+  float ks[2], vs[2];  // fp8, two-wavefront pass: dequantisation scales of those pages, fetched along with the rows
   bool valid;
 };
 
@@ -1049,6 +1050,7 @@ __device__ __forceinline__ Flight issue_next_half(const KvView& kv, Cursor& c, i
   f.pages[0] = f.pages[1] = 0;
   if (!c.live) return f;
   issue_half<FP8>(kv, c.sg, f.tb, half, c.pw, geo, lane, rk, rv, f.pages);
+  if constexpr (FP8) { half_scales(kv, c.sg.g, f.pages, kv.k_scale, f.ks); half_scales(kv, c.sg.g, f.pages, kv.v_scale, f.vs); }
   advance_cursor(kv, c, lane);
   return f;
 }
@@ -1139,10 +1141,11 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
   Cursor cur = open_cursor(kv, ws, blockIdx.x, lane);
   if (!cur.live) return;                       // the same for both wavefronts
   int unit = cur.unit;
-  // half tiles in flight per wavefront: two where the registers allow it (3 row blocks of bf16: 402 against 414 us
-  // for 16 requests of 24-32 K tokens; 4 row blocks would spill).  fp8 has the room as well but gains nothing from
-  // it (419 against 415 us at 64 requests): its tiles are bound by their arithmetic and barriers, not by latency.
-  constexpr int DEPTH = (!FP8 && RB == 3) ? 2 : 1;
+  // Half tiles in flight per wavefront: two where the registers allow it.  Three row blocks of bf16: 402 against
+  // 414 us at 16 requests of 24-32 K tokens (four row blocks would spill).  fp8: the dequantisation scales of a
+  // tile must then be fetched along with its rows (issue_next_half), or their load at the tile's turn keeps a
+  // round trip to memory in every tile: 394 against 415 us at 64 requests, neither change gains anything alone.
+  constexpr int DEPTH = (FP8 || RB == 3) ? 2 : 1;
   u32x4 rk[DEPTH][kHalf], rv[DEPTH][kHalf];
   Flight fl[DEPTH];
 #pragma unroll
@@ -1225,7 +1228,7 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
     const int tb = f.tb;
     half_to_lds<FP8, false>(rk, s_tile, lane, half);
     float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
-    if constexpr (FP8) { half_scales(kv, cs.g, f.pages, kv.k_scale, ks); half_scales(kv, cs.g, f.pages, kv.v_scale, vs); }
+    if constexpr (FP8) { ks[0] = f.ks[0]; ks[1] = f.ks[1]; vs[0] = f.vs[0]; vs[1] = f.vs[1]; }
     __syncthreads();                           // the K tile (and Q) is complete
     f32x4 s[2][RBW];
     if constexpr (kQRegs) {
