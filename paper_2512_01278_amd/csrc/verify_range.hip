@@ -236,9 +236,19 @@ struct Flight {
   Segment sg;
   int tb;            // first token of the tile
   int pages[2];      // pages of its two 16-token halves
-  float ks[2], vs[2];  // fp8, two-wavefront pass: dequantisation scales of those pages, fetched along with the rows
+  float ks[2], vs[2];  // fp8: dequantisation scales of those pages, fetched along with the rows (a load at the
+                     // tile's turn would keep a round trip to memory in every tile)
   bool valid;
 };
+
+template <bool FP8>
+__device__ __forceinline__ void fetch_scales(const KvView& kv, Flight& f) {
+  f.ks[0] = f.ks[1] = f.vs[0] = f.vs[1] = 1.f;
+  if constexpr (FP8) {
+    half_scales(kv, f.sg.g, f.pages, kv.k_scale, f.ks);
+    half_scales(kv, f.sg.g, f.pages, kv.v_scale, f.vs);
+  }
+}
 
 // Issue side of the tile stream of one range.  The stream runs ahead of the arithmetic by the
 // tiles in flight and crosses pair boundaries without draining: when it enters a pair it already
@@ -446,8 +456,10 @@ __device__ __forceinline__ Flight issue_next(const KvView& kv, Cursor& c, const 
   f.sg = c.sg;
   f.tb = c.tile * kTileTokens;
   f.pages[0] = f.pages[1] = 0;
+  f.ks[0] = f.ks[1] = f.vs[0] = f.vs[1] = 1.f;
   if (!c.live) return f;
   issue_tile<FP8, true, WITH_V>(kv, c.sg, f.tb, c.pw, geo, lane, rk, rv, f.pages);
+  fetch_scales<FP8>(kv, f);
   advance_cursor(kv, c, lane);
   return f;
 }
@@ -463,8 +475,10 @@ __device__ __forceinline__ Flight issue_next_k(const KvView& kv, Cursor& c, cons
   f.sg = c.sg;
   f.tb = c.tile * kTileTokens;
   f.pages[0] = f.pages[1] = 0;
+  f.ks[0] = f.ks[1] = f.vs[0] = f.vs[1] = 1.f;
   if (!c.live) return f;
   issue_tile<FP8, true, false>(kv, c.sg, f.tb, c.pw, geo, lane, rk, rv, f.pages);
+  fetch_scales<FP8>(kv, f);
   return f;
 }
 template <bool FP8>
@@ -521,8 +535,7 @@ __global__ __launch_bounds__(kThreads, 2) void verify_lse_range(KvView kv, const
     }
     const int tb = f.tb;
     rows_to_lds<FP8, false>(regs, s_tile, lane);
-    float ks[2] = {1.f, 1.f};
-    if constexpr (FP8) half_scales(kv, cs.g, f.pages, kv.k_scale, ks);
+    const float ks[2] = {f.ks[0], f.ks[1]};
     f = issue_next<FP8, false>(kv, cur, geo, lane, regs, unused);
     f32x4 s[2][RB];
     tile_qk<RB>(s_tile, qf, s, lane);
@@ -681,8 +694,7 @@ __global__ __launch_bounds__(kThreads, RB >= 3 ? 1 : 2) void verify_score_range(
     }
     const int tb = f.tb;
     rows_to_lds<FP8, false>(rk, s_tile, lane);
-    float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
-    if constexpr (FP8) { half_scales(kv, cs.g, f.pages, kv.k_scale, ks); half_scales(kv, cs.g, f.pages, kv.v_scale, vs); }
+    const float ks[2] = {f.ks[0], f.ks[1]}, vs[2] = {f.vs[0], f.vs[1]};
     f32x4 s[2][RB];
     tile_qk_ldsq<RB>(s_tile, s_q, R, s, lane);
     // the K rows are consumed: the V rows take their place, and both register sets carry the next tile
@@ -892,8 +904,7 @@ __device__ __forceinline__ void flash_range_body(const KvView& kv, const uint16_
     }
     const int tb = f.tb;
     rows_to_lds<FP8, false>(rk, s_tile, lane);
-    float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
-    if constexpr (FP8) { half_scales(kv, cs.g, f.pages, kv.k_scale, ks); half_scales(kv, cs.g, f.pages, kv.v_scale, vs); }
+    const float ks[2] = {f.ks[0], f.ks[1]}, vs[2] = {f.vs[0], f.vs[1]};
     f = issue_next_k<FP8>(kv, cur, geo, lane, rk, rv);       // the K registers are free: next tile's K rows leave now
     f32x4 s[2][RB];
     tile_qk_ldsq<RB>(s_tile, s_q, R, s, lane);
@@ -1048,9 +1059,10 @@ __device__ __forceinline__ Flight issue_next_half(const KvView& kv, Cursor& c, i
   f.sg = c.sg;
   f.tb = c.tile * kTileTokens;
   f.pages[0] = f.pages[1] = 0;
+  f.ks[0] = f.ks[1] = f.vs[0] = f.vs[1] = 1.f;
   if (!c.live) return f;
   issue_half<FP8>(kv, c.sg, f.tb, half, c.pw, geo, lane, rk, rv, f.pages);
-  if constexpr (FP8) { half_scales(kv, c.sg.g, f.pages, kv.k_scale, f.ks); half_scales(kv, c.sg.g, f.pages, kv.v_scale, f.vs); }
+  fetch_scales<FP8>(kv, f);
   advance_cursor(kv, c, lane);
   return f;
 }
@@ -1227,8 +1239,7 @@ __device__ __forceinline__ void flash_pair_wave(const KvView& kv, const uint16_t
     }
     const int tb = f.tb;
     half_to_lds<FP8, false>(rk, s_tile, lane, half);
-    float ks[2] = {1.f, 1.f}, vs[2] = {1.f, 1.f};
-    if constexpr (FP8) { ks[0] = f.ks[0]; ks[1] = f.ks[1]; vs[0] = f.vs[0]; vs[1] = f.vs[1]; }
+    const float ks[2] = {f.ks[0], f.ks[1]}, vs[2] = {f.vs[0], f.vs[1]};
     __syncthreads();                           // the K tile (and Q) is complete
     f32x4 s[2][RBW];
     if constexpr (kQRegs) {

@@ -50,6 +50,9 @@ def test_config1_tiny_fp32():
     (116, dict(spec_k=15, Hq=8, Hkv=2, seq_lens=[16, 130, 1100], budgets=[16, 40, 64])),
     (117, dict(spec_k=3, Hq=16, Hkv=1, seq_lens=[4, 257, 600], budgets=[4, 64, 64])),
     (118, dict(kv_dtype="fp8_e4m3", spec_k=5, Hq=16, Hkv=2, seq_lens=[6, 255, 1000], budgets=[6, 16, 128])),
+    # fp8 KV through the one-wavefront pass: 20 rows (2 row blocks) and 6 rows (1 row block)
+    (119, dict(kv_dtype="fp8_e4m3", spec_k=4, Hq=8, Hkv=2, seq_lens=[33, 700, 2100], budgets=[8, 64, 128])),
+    (120, dict(kv_dtype="fp8_e4m3", spec_k=2, Hq=4, Hkv=2, seq_lens=[7, 300, 1500], budgets=[7, 32, 64])),
 ])
 def test_small_shapes(seed, kw):
     round_trip(small(seed, **kw))
