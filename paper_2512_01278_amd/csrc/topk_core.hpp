@@ -82,6 +82,7 @@ __device__ __forceinline__ void select_topk_in_registers(const uint32_t (&key)[C
   const int t0 = static_cast<int>(threadIdx.x) * KPC;
   uint32_t prefix = 0, remaining = K;      // uniform across the workgroup
   const bool take_all = !(K < L);
+  const int nch = (L + kChunk - 1) / kChunk;   // chunks that hold any position of this row (uniform): the others are skipped
   if (!take_all) {
 #pragma unroll
     for (int pass = 0; pass < 3; ++pass) {
@@ -98,6 +99,7 @@ __device__ __forceinline__ void select_topk_in_registers(const uint32_t (&key)[C
       uint32_t lo = 0xffffffffu, hi = 0u, mine = 0u;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
+        if (c >= nch) continue;
 #pragma unroll
         for (int j = 0; j < KPC; ++j) {
           const bool act = c * kChunk + t0 + j < L && (key[c][j] & mask) == prefix;
@@ -114,6 +116,7 @@ __device__ __forceinline__ void select_topk_in_registers(const uint32_t (&key)[C
       } else {
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
+          if (c >= nch) continue;
 #pragma unroll
           for (int j = 0; j < KPC; ++j) {
             const bool act = c * kChunk + t0 + j < L && (key[c][j] & mask) == prefix;
@@ -174,7 +177,8 @@ __device__ __forceinline__ void select_topk_in_registers(const uint32_t (&key)[C
   uint32_t n_gt[CH], n_eq[CH], s_gt[CH], s_eq[CH];
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
-    n_gt[c] = n_eq[c] = 0;
+    n_gt[c] = n_eq[c] = s_gt[c] = s_eq[c] = 0;
+    if (c >= nch) continue;
 #pragma unroll
     for (int j = 0; j < KPC; ++j) {
       const bool in = c * kChunk + t0 + j < L;
@@ -191,6 +195,7 @@ __device__ __forceinline__ void select_topk_in_registers(const uint32_t (&key)[C
   uint32_t base_gt = 0, base_eq = 0;           // keys of earlier chunks
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
+    if (c >= nch) continue;
     uint32_t b_gt = 0, b_eq = 0, t_gt = 0, t_eq = 0;
 #pragma unroll 1
     for (int w = 0; w < kWaves; ++w) {
