@@ -58,6 +58,26 @@ def test_small_shapes(seed, kw):
     round_trip(small(seed, **kw))
 
 
+def test_random_shapes_both_call_styles():
+    """24 seeded random shapes of the matrix-core paths (1 to 64 query rows per KV head, bf16 and fp8 KV, pages of
+    16 to 64 tokens, contexts from the queries' own tokens up to 30 K), as three calls and as the fused call."""
+    rng = np.random.default_rng(20251201278)
+    for it in range(24):
+        G = int(rng.choice([1, 2, 4, 8, 16])); Hkv = int(rng.choice([1, 2, 4])); k = int(rng.integers(0, 9))
+        if (k + 1) * G > 64:
+            k = 64 // G - 1
+        P = int(rng.choice([16, 32, 64])); B = int(rng.integers(1, 5))
+        kvd = str(rng.choice(["bf16", "fp8_e4m3"]))
+        pool = [int(rng.integers(1, 40)), int(rng.integers(40, 600)), int(rng.integers(600, 4000)),
+                int(rng.integers(8000, 30000)) if it % 6 == 5 else int(rng.integers(100, 900))]
+        lens = [max(k + 1, int(x)) for x in rng.choice(pool, size=B)]
+        buds = [int(min(l, rng.choice([1, 7, 32, 100, 513, 700]))) for l in lens]
+        w = gen.make_custom(name="random", seed=9100 + it, B=B, Hq=G * Hkv, Hkv=Hkv, D=128, P=P, spec_k=k, q_dtype="bf16",
+                            kv_dtype=kvd, seq_lens=lens, budgets=buds, sink_tokens=int(rng.choice([0, 4])))
+        for fused in (False, True):
+            round_trip(w, what=f"random shape {it}", fused_select=fused)
+
+
 # ------------------------ work division of the two verification passes ----
 def test_many_tiny_requests_span_ranges():
     """300 requests of 5..70 tokens: more requests than lanes in the wave-wide search for a range's
