@@ -1459,7 +1459,7 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
   // get +inf: their probabilities vanish wherever the log-sum-exp is applied.
   // 2. O of a pair cut into several segments.  The partials of up to kSegs segments are fetched before the
   // log-sum-exp is known (every thread owns up to kOuts pieces of 4 dims), so both waits overlap.
-  constexpr int kSegs = THREADS >= 1024 ? 2 : 4;
+  constexpr int kSegs = THREADS >= 1024 ? 2 : 5;
   constexpr int kOuts = (RB * 16 * (kHeadDim / 4) + THREADS - 1) / THREADS;
   const int nseg = w1 - w0 + 1;
   const bool split = w1 > w0 && lead;
@@ -1485,15 +1485,31 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
   if (threadIdx.x < rows) {
     const int row = threadIdx.x;
     float m = -INFINITY, l = 0.f;
-    for (int w = w0; w <= w1; ++w) {
-      // with fewer units than ranges some ranges are empty and own no segment
-      if (range_begin(w, total, ws.n_ranges) == range_begin(w + 1, total, ws.n_ranges)) continue;
-      const float mc = ws.part_m[static_cast<int64_t>(pair + w) * rows + row];
-      const float lc = ws.part_l[static_cast<int64_t>(pair + w) * rows + row];
+    auto add = [&](float mc, float lc) {
       const float mn = fmaxf(m, mc);
       const float mu = (mn == -INFINITY) ? 0.f : mn;
       l = l * fast_exp2(m - mu) + lc * fast_exp2(mc - mu);
       m = mn;
+    };
+    if (nseg <= kSegs && total >= ws.n_ranges) {       // all segments exist: their (m, l) leave together
+      float mc[kSegs], lc[kSegs];
+#pragma unroll
+      for (int sg = 0; sg < kSegs; ++sg) {
+        mc[sg] = -INFINITY;
+        lc[sg] = 0.f;
+        if (sg < nseg) {
+          mc[sg] = ws.part_m[static_cast<int64_t>(pair + w0 + sg) * rows + row];
+          lc[sg] = ws.part_l[static_cast<int64_t>(pair + w0 + sg) * rows + row];
+        }
+      }
+#pragma unroll
+      for (int sg = 0; sg < kSegs; ++sg) add(mc[sg], lc[sg]);     // an absent segment adds exp2(-inf) * 0
+    } else {
+      for (int w = w0; w <= w1; ++w) {
+        // with fewer units than ranges some ranges are empty and own no segment
+        if (range_begin(w, total, ws.n_ranges) == range_begin(w + 1, total, ws.n_ranges)) continue;
+        add(ws.part_m[static_cast<int64_t>(pair + w) * rows + row], ws.part_l[static_cast<int64_t>(pair + w) * rows + row]);
+      }
     }
     const bool live = row < Rb && l > 0.f;
     const float v = live ? m + log2f(l) : INFINITY;
