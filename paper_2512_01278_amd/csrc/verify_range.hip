@@ -1587,7 +1587,6 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
   uint32_t key[CH][KPC];
   auto chunk = [&](int c, uint32_t (&keys)[KPC]) {
     const int t_begin = c * kChunkTiles, t_end = min(tiles, t_begin + kChunkTiles);
-    if (c != my_chunk) prime(c);
     for (int tile = t_begin + wave; tile < t_end;) {
 #pragma unroll
       for (int i = 0; i < kBufs; ++i) {
@@ -1598,6 +1597,7 @@ __global__ __launch_bounds__(THREADS) void verify_finish(KvView kv, int n_q, Ran
         }
       }
     }
+    if (!SPLIT && (c + 1) * kChunk < L) prime(c + 1);   // the next chunk's first tiles leave before the barriers
     __syncthreads();
     const int p0 = c * kChunk + static_cast<int>(threadIdx.x) * KPC;      // this thread's 8 positions
 #pragma unroll
